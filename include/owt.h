@@ -1,0 +1,158 @@
+/*
+ * owt.h -- C ABI of libowt: one worker's compute hot path of the training
+ * scheme of "One weird trick for parallelizing convolutional neural networks"
+ * on one AMD MI355X (gfx950).
+ *
+ * In that scheme (Section 4) every worker runs all convolutional layers
+ * data-parallel on its own batch (about 128 examples; forward steps 1-2,
+ * backward step 2) and owns 1/K of the neurons of every fully-connected
+ * layer (forward step 3, backward step 1).  This library is that per-worker
+ * computation: convolution forward / backward-data / backward-filter with a
+ * fused bias+ReLU, the worker's fully-connected column shard forward and
+ * backward, and the max-pooling that sits between the convolution layers of
+ * the Section 5 model.  Exchanges between workers are not part of it.
+ *
+ * Conventions for every call
+ *  - All data pointers are DEVICE pointers, 16-byte aligned, dense row-major:
+ *    activations NHWC [n][h][w][c], filters KRSC [k][r][s][c], fully-connected
+ *    weights [o][i].  The caller owns every buffer; the library never
+ *    allocates, frees or keeps a pointer.  Buffers must not alias unless
+ *    stated otherwise.
+ *  - Work is enqueued on `hip_stream` (a hipStream_t cast to void*, NULL = the
+ *    default stream) and the call returns without waiting for it.
+ *  - `ws` is caller-provided device scratch of at least the number of bytes the
+ *    matching *_workspace_bytes query returns (may be NULL when that is 0).
+ *    Its contents are undefined after the call.
+ *  - Return value OWT_OK, or an error code; on error nothing was launched and
+ *    no output was touched.  owt_last_error() gives a message for the calling
+ *    thread's most recent error.
+ *  - Results are deterministic run to run (no floating-point atomics).
+ *  - dtype names the STORAGE type of x, w, y, dy, dx.  Products are
+ *    accumulated in fp32; bias, dw and dbias are always fp32.  bf16 results are
+ *    rounded to nearest-even once, when stored.
+ *  - Output size P = floor((H + 2*pad_h - R)/stride_h) + 1, Q likewise.
+ */
+#ifndef OWT_H
+#define OWT_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    OWT_OK = 0,
+    OWT_EINVAL = 1,       /* bad descriptor, null or misaligned pointer                  */
+    OWT_EUNSUPPORTED = 2, /* valid request this build has no kernel for                  */
+    OWT_EWORKSPACE = 3,   /* ws_bytes smaller than the workspace query                   */
+    OWT_ELAUNCH = 4       /* the HIP runtime refused a launch (message has the HIP text) */
+} owt_status;
+
+typedef enum { OWT_F32 = 0, OWT_BF16 = 1 } owt_dtype;
+
+enum { OWT_BIAS = 1u, OWT_RELU = 2u };
+
+enum { OWT_PASS_FWD = 0, OWT_PASS_BWD_DATA = 1, OWT_PASS_BWD_FILTER = 2 };
+
+/* One convolution layer on a batch of N images (Section 4, forward step 2). */
+typedef struct {
+    int N, C, H, W;         /* input batch, channels, height, width          */
+    int K, R, S;            /* filters, filter height, filter width          */
+    int stride_h, stride_w; /* >= 1                                          */
+    int pad_h, pad_w;       /* zero padding on each side, 0 <= pad < R (S)   */
+    owt_dtype dtype;
+    unsigned flags;         /* OWT_BIAS | OWT_RELU                           */
+} owt_conv_desc;
+
+/* One fully-connected layer split by output column over `workers` workers
+ * (Section 4, forward step 3: each worker holds 1/K of the neurons; the
+ * Section 5.1 footnote sizes the K = 8 shard at 4096 x 512).  This worker owns
+ * O_local = O_total / workers columns; `w` is its [O_local][I] block. */
+typedef struct {
+    int N;       /* batch the shard runs on (128 in schemes (b) and (c)) */
+    int I;       /* inputs                                               */
+    int O_total; /* outputs of the whole layer, divisible by workers     */
+    int workers; /* K                                                    */
+    int rank;    /* 0 <= rank < workers (checked, otherwise unused)      */
+    owt_dtype dtype;
+    unsigned flags; /* OWT_BIAS | OWT_RELU                               */
+} owt_fc_desc;
+
+/* Scratch bytes a pass needs (pass = OWT_PASS_*).  (size_t)-1 on a bad descriptor. */
+size_t owt_conv_workspace_bytes(const owt_conv_desc *d, int pass);
+size_t owt_fc_workspace_bytes(const owt_fc_desc *d, int pass);
+
+/* Convolution forward (Section 4, forward step 2):
+ *   y[n,p,q,k] = act(bias[k] + sum_{r,s,c} x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c] * w[k,r,s,c])
+ * taps outside the image count as 0; act = max(0,.) with OWT_RELU, identity
+ * otherwise; bias is read only with OWT_BIAS (else may be NULL).
+ * x [N,H,W,C], w [K,R,S,C], bias [K] fp32, y [N,P,Q,K] (written). */
+owt_status owt_conv_fwd(const owt_conv_desc *d, const void *x, const void *w, const float *bias,
+                        void *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Convolution backward w.r.t. the input (Section 4, backward step 2):
+ *   dz = dy * [y > 0] if the descriptor has OWT_RELU (y = the forward output, required then), else dy
+ *   dx[n,h,w,c] = sum of dz[n,p,q,k] * w[k,r,s,c] over all (p,q,k,r,s) with
+ *                 p*stride_h-pad_h+r == h and q*stride_w-pad_w+s == w
+ * dy, y [N,P,Q,K]; w [K,R,S,C]; dx [N,H,W,C] (written, every element). */
+owt_status owt_conv_bwd_data(const owt_conv_desc *d, const void *dy, const void *y_or_null,
+                             const void *w, void *dx, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Convolution backward w.r.t. filters and bias (Section 4, backward step 2):
+ *   dw[k,r,s,c] = alpha * sum_{n,p,q} dz[n,p,q,k] * x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c] + beta * dw
+ *   dbias[k]    = alpha * sum_{n,p,q} dz[n,p,q,k] + beta * dbias          (skipped when dbias_or_null is NULL)
+ * dz as in owt_conv_bwd_data.  beta == 0 overwrites without reading the old
+ * contents.  alpha = 1/N gives the batch-mean gradient the update rule of
+ * Section 5 uses; beta = 1 accumulates over several calls (Section 4.2).
+ * dw [K,R,S,C] and dbias [K] are fp32 whatever the dtype. */
+owt_status owt_conv_bwd_filter(const owt_conv_desc *d, const void *x, const void *dy,
+                               const void *y_or_null, float alpha, float beta, float *dw,
+                               float *dbias_or_null, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Fully-connected column shard forward (Section 4, forward step 3):
+ *   y[n,o] = act(bias[o] + sum_i x[n,i] * w[o,i]),  o over this worker's O_local columns.
+ * x [N,I], w [O_local,I], bias [O_local] fp32, y [N,O_local] (written). */
+owt_status owt_fc_shard_fwd(const owt_fc_desc *d, const void *x, const void *w, const float *bias,
+                            void *y, void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Fully-connected column shard backward (Section 4, backward step 1):
+ *   dz = dy * [y > 0] with OWT_RELU (y required), else dy
+ *   dx_partial[n,i] = sum_o dz[n,o] * w[o,i]     this worker's addend of the sum over workers;
+ *                                                skipped when dx_partial_or_null is NULL
+ *   dw[o,i] = alpha * sum_n dz[n,o] * x[n,i] + beta * dw;   dbias[o] likewise (NULL to skip)
+ * dy, y [N,O_local]; dx_partial [N,I]; dw [O_local,I] fp32; dbias [O_local] fp32. */
+owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, const void *y_or_null,
+                            const void *dy, float alpha, float beta, void *dx_partial_or_null,
+                            float *dw, float *dbias_or_null, void *ws, size_t ws_bytes,
+                            void *hip_stream);
+
+/* Max pooling between the convolution layers of the Section 5 model, window
+ * win x win (2..15), stride >= 1, no padding: P = floor((H-win)/stride)+1.
+ *   y[n,p,q,c] = max_{r,s<win} x[n, p*stride+r, q*stride+s, c]
+ *   argmax[n,p,q,c] = r*win+s of the first maximum in row-major (r,s) order.
+ * x [N,H,W,C], y [N,P,Q,C], argmax [N,P,Q,C] bytes (both written). */
+owt_status owt_maxpool_fwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                           const void *x, void *y, unsigned char *argmax, void *hip_stream);
+
+/* Max pooling backward: dx[n,h,w,c] = sum of dy[n,p,q,c] over the windows
+ * (p,q) whose argmax names (h,w); dx [N,H,W,C] is written everywhere. */
+owt_status owt_maxpool_bwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                           const void *dy, const unsigned char *argmax, void *dx, void *hip_stream);
+
+/* Message for the calling thread's most recent non-OK return ("" if none).
+ * Points at thread-local static storage; valid until the thread's next call. */
+const char *owt_last_error(void);
+
+/* Library ABI version (bumped on any signature change). */
+int owt_abi_version(void);
+
+/* Host-only self check of the index arithmetic helpers and the tile planner
+ * (no GPU needed).  Returns 0 when everything holds; otherwise non-zero and
+ * owt_last_error() names the failing case. */
+int owt_selftest_host(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OWT_H */

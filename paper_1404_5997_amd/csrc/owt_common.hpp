@@ -1,0 +1,84 @@
+// Shared host/device definitions of libowt (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace owt {
+
+// Exact unsigned division of any n < 2^31 by a fixed d >= 1 with one 64-bit
+// multiply: l = ceil(log2 d), m = ceil(2^(31+l) / d) fits 32 bits and
+// floor(n/d) == (n*m) >> (31+l)   (round-up method of Granlund & Montgomery).
+struct FastDiv {
+    uint32_t m, sh, d;
+    __host__ void set(uint32_t dv)
+    {
+        d = dv;
+        uint32_t l = 0;
+        while ((1ull << l) < dv) l++;
+        sh = 31 + l;
+        m = (uint32_t)(((1ull << sh) + dv - 1) / dv);
+    }
+    __host__ __device__ __forceinline__ uint32_t div(uint32_t n) const
+    {
+        return (uint32_t)(((uint64_t)n * m) >> sh);
+    }
+};
+
+// Geometry of one convolution seen as a GEMM.  Fully-connected layers are the
+// H = W = R = S = 1 case.
+struct Geom {
+    int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
+    FastDiv dC, dS, dK, dQ, dPQ, dW, dHW, dsh, dsw;
+};
+
+struct GemmParams {
+    Geom g;
+    int M, Ncols, Kd;        // GEMM extents of this pass
+    const void *a, *b;       // tensors the A and B operands are gathered from
+    const void *mask;        // forward output y (ReLU mask of the dz operand) or null
+    void *out;               // result tensor (used when splits == 1)
+    float *partial;          // [splits][M][Ncols] fp32 (used when splits > 1)
+    const float *bias;       // forward epilogue
+    float alpha, beta;       // filter-gradient epilogue
+    float *dbias;            // bias gradient (filter pass), may be null
+    float *dbias_partial;    // [splits][M] fp32 when splits > 1
+    int splits, ksteps, ksteps_per_split;
+    int tiles_m, tiles_n;
+    unsigned flags;
+};
+
+struct bf16_t { uint16_t bits; };
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// fp32 -> bf16, round to nearest even; NaN stays NaN.
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7f800000u) == 0x7f800000u && (u & 0x007fffffu)) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float4 load4(const float *p, int off) { return *(const float4 *)(p + off); }
+__device__ __forceinline__ float4 load4(const bf16_t *p, int off)
+{
+    const uint2 v = *(const uint2 *)(p + off);
+    return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
+                       __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
+}
+__device__ __forceinline__ float load1(const float *p, int off) { return p[off]; }
+__device__ __forceinline__ float load1(const bf16_t *p, int off) { return bf16_to_f32(p[off].bits); }
+
+__device__ __forceinline__ void store1(float *p, size_t off, float v) { p[off] = v; }
+__device__ __forceinline__ void store1(bf16_t *p, size_t off, float v) { p[off].bits = f32_to_bf16(v); }
+__device__ __forceinline__ void store2(float *p, size_t off, float v0, float v1)
+{
+    *(float2 *)(p + off) = make_float2(v0, v1);
+}
+__device__ __forceinline__ void store2(bf16_t *p, size_t off, float v0, float v1)
+{
+    *(uint32_t *)(p + off) = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+}
+
+}  // namespace owt

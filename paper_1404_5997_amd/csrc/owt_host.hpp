@@ -1,0 +1,48 @@
+// Host-side helpers of libowt: error reporting, descriptor checks, tile planning.
+#pragma once
+#include <stdarg.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "../../include/owt.h"
+#include "owt_common.hpp"
+
+namespace owt {
+
+owt_status fail(owt_status st, const char *fmt, ...);
+void clear_error();
+
+inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
+
+// Tile shapes the implicit-GEMM kernel is instantiated for.
+struct TileInfo { int id, WM, WN, BK; float eff; };
+enum { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x128 = 2, TILE_64x64 = 3, NUM_TILES = 4 };
+extern const TileInfo kTiles[NUM_TILES];
+
+struct Plan {
+    int tile, splits, ksteps, ksteps_per_split, tiles_m, tiles_n;
+    size_t partial_bytes, dbias_partial_bytes;   // workspace, in this order
+    size_t total_bytes() const { return partial_bytes + dbias_partial_bytes; }
+};
+
+// Chooses tile shape and split-K factor for a GEMM view of M x Ncols x Kd.
+// vec_ok == false restricts the choice to the scalar-gather instantiation.
+Plan plan_gemm(long M, long Ncols, long Kd, bool vec_ok, bool want_dbias);
+
+bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw);
+
+// One entry per (pass, storage type); defined in igemm_inst.hip, built once per pair.
+typedef hipError_t (*LaunchFn)(int tile, int va, int vb, const GemmParams &p, hipStream_t s);
+hipError_t owt_launch_fwd_f32(int, int, int, const GemmParams &, hipStream_t);
+hipError_t owt_launch_fwd_bf16(int, int, int, const GemmParams &, hipStream_t);
+hipError_t owt_launch_data_f32(int, int, int, const GemmParams &, hipStream_t);
+hipError_t owt_launch_data_bf16(int, int, int, const GemmParams &, hipStream_t);
+hipError_t owt_launch_filter_f32(int, int, int, const GemmParams &, hipStream_t);
+hipError_t owt_launch_filter_bf16(int, int, int, const GemmParams &, hipStream_t);
+
+// Runs one planned GEMM pass (main kernel + split-K reduction when needed).
+owt_status run_pass(int pass, owt_dtype dt, int va, int vb, GemmParams &p, const Plan &pl,
+                    void *ws, hipStream_t s);
+
+}  // namespace owt

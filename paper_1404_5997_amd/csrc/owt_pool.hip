@@ -1,0 +1,143 @@
+// Max pooling forward/backward, NHWC, HBM-bound: one thread per 4 channels (or 1
+// when C is not a multiple of 4), consecutive threads on consecutive channels.
+#include "owt_host.hpp"
+
+namespace owt {
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y,
+                                                          unsigned char *__restrict__ am, int N, int H, int W,
+                                                          int C, int win, int st, int P, int Q, FastDiv dCv,
+                                                          FastDiv dQ, FastDiv dP)
+{
+    const int Cv = C / V;
+    const long total = (long)N * P * Q * Cv;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int pix = dCv.div((uint32_t)i), cv = (int)i - pix * Cv;
+        const int np = dQ.div(pix), q = pix - np * Q;
+        const int n = dP.div(np), p = np - n * P;
+        const int c = cv * V;
+        float best[V]; int bi[V];
+        const int base = ((n * H + p * st) * W + q * st) * C + c;
+        for (int r = 0; r < win; r++)
+            for (int s = 0; s < win; s++) {
+                const int off = base + (r * W + s) * C;
+                float v[V];
+                if constexpr (V == 4) { const float4 t = load4(x, off); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+                else v[0] = load1(x, off);
+#pragma unroll
+                for (int j = 0; j < V; j++)
+                    if ((r | s) == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = r * win + s; }
+            }
+        const size_t o = (size_t)pix * C + c;
+#pragma unroll
+        for (int j = 0; j < V; j++) { store1(y, o + j, best[j]); am[o + j] = (unsigned char)bi[j]; }
+    }
+}
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) maxpool_bwd_kernel(const T *__restrict__ dy,
+                                                          const unsigned char *__restrict__ am, T *__restrict__ dx,
+                                                          int N, int H, int W, int C, int win, int st, int P, int Q,
+                                                          FastDiv dCv, FastDiv dW, FastDiv dH, FastDiv dst)
+{
+    const int Cv = C / V;
+    const long total = (long)N * H * W * Cv;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int pix = dCv.div((uint32_t)i), cv = (int)i - pix * Cv;
+        const int nh = dW.div(pix), w = pix - nh * W;
+        const int n = dH.div(nh), h = nh - n * H;
+        const int c = cv * V;
+        // windows p with p*st <= h <= p*st + win - 1
+        const int p_hi = min(P - 1, (int)dst.div(h)), q_hi = min(Q - 1, (int)dst.div(w));
+        const int p_lo = h >= win ? (int)dst.div(h - win + st) : 0;   // ceil((h-win+1)/st)
+        const int q_lo = w >= win ? (int)dst.div(w - win + st) : 0;
+        float acc[V];
+#pragma unroll
+        for (int j = 0; j < V; j++) acc[j] = 0.f;
+        for (int p = p_lo; p <= p_hi; p++)
+            for (int q = q_lo; q <= q_hi; q++) {
+                const int code = (h - p * st) * win + (w - q * st);
+                const int off = ((n * P + p) * Q + q) * C + c;
+                if constexpr (V == 4) {
+                    const uint32_t a4 = *(const uint32_t *)(am + off);
+                    const float4 g = load4(dy, off);
+                    if ((int)(a4 & 255u) == code) acc[0] += g.x;
+                    if ((int)((a4 >> 8) & 255u) == code) acc[1] += g.y;
+                    if ((int)((a4 >> 16) & 255u) == code) acc[2] += g.z;
+                    if ((int)(a4 >> 24) == code) acc[3] += g.w;
+                } else if ((int)am[off] == code) {
+                    acc[0] += load1(dy, off);
+                }
+            }
+        const size_t o = (size_t)pix * C + c;
+#pragma unroll
+        for (int j = 0; j < V; j++) store1(dx, o + j, acc[j]);
+    }
+}
+
+static owt_status check_pool(int N, int H, int W, int C, int win, int st, owt_dtype dt, int &P, int &Q)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0) return fail(OWT_EINVAL, "N,H,W,C must be positive");
+    if (win < 2 || win > 15) return fail(OWT_EINVAL, "win must be in 2..15");
+    if (st < 1) return fail(OWT_EINVAL, "stride must be >= 1");
+    if (H < win || W < win) return fail(OWT_EINVAL, "window larger than the input");
+    if (dt != OWT_F32 && dt != OWT_BF16) return fail(OWT_EINVAL, "unknown dtype %d", (int)dt);
+    if ((long)N * H * W * C > 0x7fffffffL) return fail(OWT_EUNSUPPORTED, "tensor with more than 2^31-1 elements");
+    P = (H - win) / st + 1; Q = (W - win) / st + 1;
+    return OWT_OK;
+}
+
+static int grid_for(long total) { long b = (total + 255) / 256; return (int)(b > 65536 ? 65536 : (b < 1 ? 1 : b)); }
+
+}  // namespace owt
+
+using namespace owt;
+
+extern "C" {
+
+owt_status owt_maxpool_fwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                           const void *x, void *y, unsigned char *argmax, void *hip_stream)
+{
+    int P, Q;
+    owt_status st = check_pool(N, H, W, C, win, stride, dtype, P, Q);
+    if (st != OWT_OK) return st;
+    if (!x || !y || !argmax) return fail(OWT_EINVAL, "x, y or argmax is NULL");
+    if (!aligned16(x) || !aligned16(y) || !aligned16(argmax)) return fail(OWT_EINVAL, "misaligned pointer");
+    const int V = C % 4 == 0 ? 4 : 1;
+    FastDiv dCv, dQ, dP; dCv.set(C / V); dQ.set(Q); dP.set(P);
+    const long total = (long)N * P * Q * (C / V);
+    hipStream_t s = (hipStream_t)hip_stream;
+#define OWT_POOL_F(T, VV) hipLaunchKernelGGL((maxpool_fwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \
+        (const T *)x, (T *)y, argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP)
+    if (dtype == OWT_F32) { if (V == 4) OWT_POOL_F(float, 4); else OWT_POOL_F(float, 1); }
+    else { if (V == 4) OWT_POOL_F(bf16_t, 4); else OWT_POOL_F(bf16_t, 1); }
+#undef OWT_POOL_F
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(OWT_ELAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
+    return OWT_OK;
+}
+
+owt_status owt_maxpool_bwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                           const void *dy, const unsigned char *argmax, void *dx, void *hip_stream)
+{
+    int P, Q;
+    owt_status st = check_pool(N, H, W, C, win, stride, dtype, P, Q);
+    if (st != OWT_OK) return st;
+    if (!dy || !dx || !argmax) return fail(OWT_EINVAL, "dy, dx or argmax is NULL");
+    if (!aligned16(dy) || !aligned16(dx) || !aligned16(argmax)) return fail(OWT_EINVAL, "misaligned pointer");
+    const int V = C % 4 == 0 ? 4 : 1;
+    FastDiv dCv, dW, dH, dst; dCv.set(C / V); dW.set(W); dH.set(H); dst.set(stride);
+    const long total = (long)N * H * W * (C / V);
+    hipStream_t s = (hipStream_t)hip_stream;
+#define OWT_POOL_B(T, VV) hipLaunchKernelGGL((maxpool_bwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \
+        (const T *)dy, argmax, (T *)dx, N, H, W, C, win, stride, P, Q, dCv, dW, dH, dst)
+    if (dtype == OWT_F32) { if (V == 4) OWT_POOL_B(float, 4); else OWT_POOL_B(float, 1); }
+    else { if (V == 4) OWT_POOL_B(bf16_t, 4); else OWT_POOL_B(bf16_t, 1); }
+#undef OWT_POOL_B
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(OWT_ELAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
+    return OWT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,289 @@
+"""GPU parity: every exported call of libowt against the CPU oracle, element by
+element, on the same seeded inputs.  Tolerance (per output tensor):
+max|gpu - ref| <= 1e-4 * max|ref| for fp32 storage, 2e-2 * max|ref| for bf16
+storage; arg-max indices and pooled maxima bit-exact.
+
+Each backward call gets the forward output y (the ReLU mask source) and the
+pooling arg-max as INPUTS, the same arrays on both sides, so every call is a
+pure function of its arguments and parity is well-posed.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import synthetic_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from gpu_util import ConvCase, assert_close, empty, owt, prep, rel_err, to_dev, to_host, workspace  # noqa: E402
+
+
+def say(*a):
+    print(*a)
+    sys.stdout.flush()
+
+
+def layer_parity(N, C, H, W, K, R, S, stride, pad, dt="f32", bias=True, relu=True, seed=0,
+                 tensors=None, alpha=1.0, beta=0.0):
+    say("case", dict(N=N, C=C, H=H, W=W, K=K, R=R, S=S, stride=stride, pad=pad, dt=dt, bias=bias, relu=relu,
+                     alpha=alpha, beta=beta, seed=seed))
+    case = ConvCase(N, C, H, W, K, R, S, stride, pad, dt, bias, relu)
+    if tensors is None:
+        g = np.random.default_rng(1000 + seed)
+        x = g.standard_normal(case.shape_x, dtype=np.float32)
+        w = g.standard_normal(case.shape_w, dtype=np.float32) * np.float32(0.05)
+        b = g.standard_normal((K,), dtype=np.float32) * np.float32(0.05)
+        dy = g.standard_normal(case.shape_y, dtype=np.float32)
+    else:
+        x, w, b, dy = tensors
+    x, w, dy = prep(x, dt), prep(w, dt), prep(dy, dt)
+    rnd = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
+
+    y_ref = rnd(oracle.conv_fwd(x, w, b if bias else None, stride, pad, relu))
+    y_gpu = case.fwd(x, w, b if bias else None)
+    e_f = assert_close(y_gpu, y_ref, dt, "fwd")
+
+    y_in = y_ref if relu else None
+    dx_ref = rnd(oracle.conv_bwd_data(dy, w, (H, W), stride, pad, y=y_in))
+    dx_gpu = case.bwd_data(dy, y_in, w)
+    e_d = assert_close(dx_gpu, dx_ref, dt, "bwd_data")
+
+    dw0 = db0 = None
+    if beta != 0.0:
+        g2 = np.random.default_rng(2000 + seed)
+        dw0 = g2.standard_normal(case.shape_w, dtype=np.float32)
+        db0 = g2.standard_normal((K,), dtype=np.float32)
+    dw_ref, db_ref = oracle.conv_bwd_filter(x, dy, (R, S), stride, pad, y=y_in, alpha=alpha, beta=beta, dw=dw0, db=db0)
+    dw_gpu, db_gpu = case.bwd_filter(x, dy, y_in, alpha, beta, dw0, db0)
+    e_w = assert_close(dw_gpu, dw_ref, dt if dt == "f32" else "f32", "bwd_filter dw")   # dw is fp32 either way
+    e_b = assert_close(db_gpu, db_ref, "f32", "bwd_filter db")
+    say("  rel err fwd %.2e  bwd_data %.2e  dw %.2e  db %.2e" % (e_f, e_d, e_w, e_b))
+    return y_gpu, dx_gpu, dw_gpu, db_gpu
+
+
+# ------------------------------------------------------------ named configs ----
+
+def test_config1_small_layer_fp32():
+    geom, x, w, b, dy = si.config1()
+    layer_parity(geom["N"], geom["C"], geom["H"], geom["W"], geom["K"], geom["R"], geom["S"],
+                 geom["stride"], geom["pad"], tensors=(x, w, b, dy))
+
+
+def test_config2_batch128_layer_fp32():
+    geom, x, w, b, dy = si.config2(128)
+    layer_parity(geom["N"], geom["C"], geom["H"], geom["W"], geom["K"], geom["R"], geom["S"],
+                 geom["stride"], geom["pad"], tensors=(x, w, b, dy))
+
+
+def test_config2_shape_bf16_storage():
+    geom, x, w, b, dy = si.config2(32)
+    layer_parity(32, geom["C"], geom["H"], geom["W"], geom["K"], geom["R"], geom["S"],
+                 geom["stride"], geom["pad"], dt="bf16", tensors=(x, w, b, dy))
+
+
+# ------------------------------------------------------------- shape sweep ----
+
+SWEEP = [
+    # N, C, H, W, K, R, S, stride, pad           vector-path shapes (C%4 == 0, K%4 == 0)
+    (3, 8, 9, 11, 12, 3, 3, 1, 1),
+    (2, 16, 14, 10, 20, 5, 3, (1, 1), (2, 1)),
+    (5, 4, 23, 19, 8, 11, 11, 4, 2),              # first-layer geometry, stride 4
+    (4, 12, 15, 15, 36, 3, 3, 2, 1),
+    (2, 64, 27, 27, 192, 5, 5, 1, 2),             # second-layer shape, several tiles + ragged M
+    (130, 32, 6, 6, 72, 1, 1, 1, 0),              # 1x1
+    (2, 8, 7, 9, 4, 7, 9, 1, 0),                  # filter covers the whole map (dense layer as a conv)
+    (1, 4, 5, 5, 4, 3, 3, (2, 3), (0, 2)),
+    # scalar-gather shapes (C%4 != 0 and/or K%4 != 0)
+    (2, 3, 12, 12, 5, 3, 3, 1, 1),
+    (3, 3, 17, 17, 8, 5, 5, 2, 2),
+    (2, 8, 10, 10, 7, 3, 3, 1, 1),                # K odd: vector A in fwd, scalar dz gathers
+    (2, 5, 9, 8, 16, 3, 2, (2, 1), (1, 0)),
+    (1, 1, 8, 8, 1, 3, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SWEEP)))
+def test_layer_sweep_fp32(i):
+    N, C, H, W, K, R, S, stride, pad = SWEEP[i]
+    layer_parity(N, C, H, W, K, R, S, stride, pad, seed=i)
+
+
+@pytest.mark.parametrize("i", [0, 3, 4, 8, 10])
+def test_layer_sweep_bf16(i):
+    N, C, H, W, K, R, S, stride, pad = SWEEP[i]
+    layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", seed=100 + i)
+
+
+def test_flags_and_scaling_variants():
+    layer_parity(3, 8, 9, 9, 12, 3, 3, 1, 1, bias=False, relu=False, seed=50)
+    layer_parity(3, 8, 9, 9, 12, 3, 3, 1, 1, bias=True, relu=False, seed=51)
+    layer_parity(3, 8, 9, 9, 12, 3, 3, 1, 1, bias=False, relu=True, seed=52)
+    layer_parity(6, 8, 9, 9, 12, 3, 3, 1, 1, alpha=1.0 / 6, beta=1.0, seed=53)     # batch mean, accumulate
+    layer_parity(6, 8, 9, 9, 12, 3, 3, 1, 1, alpha=0.5, beta=-0.25, seed=54)
+
+
+@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (2, 1), (3, 1), (0, 3), (1, 4), (2, 2), (3, 8)])
+def test_every_tile_shape_and_split_k(tile, split):
+    # The planner is overridden so each instantiation and the two-pass reduction are exercised.
+    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(tile), str(split)
+    try:
+        layer_parity(4, 32, 13, 13, 136, 3, 3, 1, 1, seed=60 + tile)     # M = 676, ragged in every tile
+        layer_parity(2, 32, 13, 13, 136, 3, 3, 1, 1, dt="bf16", seed=70 + tile)
+    finally:
+        del os.environ["OWT_TILE"], os.environ["OWT_SPLITK"]
+
+
+def test_run_to_run_bit_equality():
+    # no floating-point atomics anywhere: identical bits on repeated runs, split-K included
+    geom, x, w, b, dy = si.config2(16)
+    case = ConvCase(16, 192, 13, 13, 384, 3, 3, 1, 1)
+    y = case.fwd(x, w, b)
+    a = case.bwd_filter(x, dy, y)
+    c = case.bwd_filter(x, dy, y)
+    np.testing.assert_array_equal(a[0], c[0])
+    np.testing.assert_array_equal(a[1], c[1])
+    np.testing.assert_array_equal(case.bwd_data(dy, y, w), case.bwd_data(dy, y, w))
+    np.testing.assert_array_equal(case.fwd(x, w, b), y)
+
+
+def test_beta_zero_never_reads_old_gradient():
+    case = ConvCase(2, 8, 6, 6, 8, 3, 3, 1, 1, relu=False, bias=False)
+    g = np.random.default_rng(5)
+    x = g.standard_normal(case.shape_x, dtype=np.float32)
+    dy = g.standard_normal(case.shape_y, dtype=np.float32)
+    nan_w = np.full(case.shape_w, np.nan, dtype=np.float32)
+    dw, db = case.bwd_filter(x, dy, None, 1.0, 0.0, nan_w, np.full((8,), np.nan, dtype=np.float32))
+    assert np.isfinite(dw).all() and np.isfinite(db).all()
+
+
+# ------------------------------------------------------ fully-connected shard ----
+
+def fc_parity(N, I, O_total, workers, relu, dt="f32", seed=0, tensors=None, alpha=1.0, beta=0.0):
+    m = owt()
+    O = O_total // workers
+    say("fc case", dict(N=N, I=I, O_total=O_total, workers=workers, O_local=O, relu=relu, dt=dt))
+    if tensors is None:
+        g = np.random.default_rng(3000 + seed)
+        x = g.standard_normal((N, I), dtype=np.float32)
+        w = g.standard_normal((O, I), dtype=np.float32) * np.float32(0.02)
+        b = g.standard_normal((O,), dtype=np.float32) * np.float32(0.02)
+        dy = g.standard_normal((N, O), dtype=np.float32)
+    else:
+        x, w, b, dy = tensors
+    x, w, dy = prep(x, dt), prep(w, dt), prep(dy, dt)
+    rnd = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
+    flags = m.OWT_BIAS | (m.OWT_RELU if relu else 0)
+    d = m.fc_desc(N, I, O_total, workers, 0, m.OWT_BF16 if dt == "bf16" else m.OWT_F32, flags)
+
+    y_ref = rnd(oracle.fc_fwd(x, w, b, relu))
+    y = empty((N, O), dt)
+    m.owt_fc_shard_fwd(d, to_dev(x, dt), to_dev(w, dt), to_dev(b), y, workspace(m.owt_fc_workspace_bytes(d, 0)))
+    e_f = assert_close(to_host(y), y_ref, dt, "fc fwd")
+
+    y_in = y_ref if relu else None
+    dw0 = db0 = None
+    if beta != 0.0:
+        g2 = np.random.default_rng(4000 + seed)
+        dw0 = g2.standard_normal((O, I), dtype=np.float32); db0 = g2.standard_normal((O,), dtype=np.float32)
+    dx_ref, dw_ref, db_ref = oracle.fc_bwd(x, w, dy, y=y_in, alpha=alpha, beta=beta, dw=dw0, db=db0)
+    dx_ref = rnd(dx_ref)
+    dx = empty((N, I), dt)
+    dw = to_dev(dw0) if dw0 is not None else torch.full((O, I), float("nan"), device="cuda")
+    db = to_dev(db0) if db0 is not None else torch.full((O,), float("nan"), device="cuda")
+    m.owt_fc_shard_bwd(d, to_dev(x, dt), to_dev(w, dt), to_dev(y_in, dt), to_dev(dy, dt), alpha, beta, dx, dw, db,
+                       workspace(m.owt_fc_workspace_bytes(d, 1)))
+    torch.cuda.synchronize()
+    e_d = assert_close(to_host(dx), dx_ref, dt, "fc dx_partial")
+    e_w = assert_close(to_host(dw), dw_ref, "f32", "fc dw")
+    e_b = assert_close(to_host(db), db_ref, "f32", "fc db")
+    say("  rel err fwd %.2e  dx %.2e  dw %.2e  db %.2e" % (e_f, e_d, e_w, e_b))
+
+
+@pytest.mark.parametrize("layer", [0, 1, 2])
+def test_fc_shard_real_shapes_fp32(layer):
+    # 9216->4096->4096->1000 over 8 workers: 512 / 512 / 125 columns, batch 128
+    L = si.FC_LAYERS[layer]
+    ws, bs = si.fc_params(4)
+    x = si.normal(4, 60 + layer, (128, L["I"]))
+    dy = si.upstream_grad(4, 70 + layer, (128, L["O_local"]))
+    fc_parity(128, L["I"], L["O_total"], si.FC_WORKERS, L["relu"], tensors=(x, ws[layer], bs[layer], dy))
+
+
+def test_fc_shard_small_and_ragged():
+    fc_parity(5, 36, 24, 2, True, seed=1)
+    fc_parity(7, 33, 15, 3, False, seed=2)                       # I, O_local odd
+    fc_parity(130, 260, 140, 1, True, seed=3, alpha=1.0 / 130, beta=1.0)
+    fc_parity(16, 64, 1000, 8, False, dt="bf16", seed=4)
+    fc_parity(128, 4096, 4096, 8, True, dt="bf16", seed=5)
+
+
+def test_fc_shard_bwd_without_dx_or_dbias():
+    m = owt()
+    g = np.random.default_rng(9)
+    x = g.standard_normal((8, 32), dtype=np.float32); w = g.standard_normal((16, 32), dtype=np.float32)
+    dy = g.standard_normal((8, 16), dtype=np.float32)
+    d = m.fc_desc(8, 32, 16, 1, 0, m.OWT_F32, 0)
+    dw = torch.full((16, 32), float("nan"), device="cuda")
+    m.owt_fc_shard_bwd(d, to_dev(x), to_dev(w), None, to_dev(dy), 1.0, 0.0, None, dw, None,
+                       workspace(m.owt_fc_workspace_bytes(d, 1)))
+    torch.cuda.synchronize()
+    assert_close(to_host(dw), oracle.fc_bwd(x, w, dy, want_dx=False, want_db=False)[1], "f32", "dw only")
+
+
+# ------------------------------------------------------------------ pooling ----
+
+@pytest.mark.parametrize("N,H,W,C,win,st,dt", [
+    (3, 13, 13, 8, 3, 2, "f32"), (2, 55, 55, 64, 3, 2, "f32"), (2, 9, 12, 5, 3, 2, "f32"),
+    (2, 10, 7, 4, 2, 2, "f32"), (1, 8, 8, 3, 4, 1, "f32"), (2, 27, 27, 192, 3, 2, "bf16"), (2, 7, 7, 3, 3, 2, "bf16"),
+])
+def test_maxpool_parity(N, H, W, C, win, st, dt):
+    m = owt()
+    say("pool case", (N, H, W, C, win, st, dt))
+    g = np.random.default_rng(77)
+    x = prep(np.maximum(g.standard_normal((N, H, W, C), dtype=np.float32), 0), dt)   # post-ReLU: many exact ties at 0
+    y_ref, am_ref = oracle.maxpool_fwd(x, win, st)
+    P, Q = y_ref.shape[1:3]
+    code = m.OWT_BF16 if dt == "bf16" else m.OWT_F32
+    y = empty((N, P, Q, C), dt); am = torch.empty((N, P, Q, C), device="cuda", dtype=torch.uint8)
+    m.owt_maxpool_fwd(N, H, W, C, win, st, code, to_dev(x, dt), y, am)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(to_host(y), y_ref)             # a max is exact
+    np.testing.assert_array_equal(am.cpu().numpy(), am_ref)      # first maximum in scan order
+    dy = prep(g.standard_normal((N, P, Q, C), dtype=np.float32), dt)
+    dx_ref = oracle.maxpool_bwd(dy, am_ref, (H, W), win, st)
+    if dt == "bf16":
+        dx_ref = oracle.round_bf16(dx_ref)
+    dx = empty((N, H, W, C), dt)
+    m.owt_maxpool_bwd(N, H, W, C, win, st, code, to_dev(dy, dt), to_dev(am_ref), dx)
+    torch.cuda.synchronize()
+    assert_close(to_host(dx), dx_ref, dt, "maxpool bwd")
+
+
+# -------------------------------------------------------------- error paths ----
+
+def test_error_codes_leave_outputs_untouched():
+    m = owt()
+    d = m.conv_desc(2, 8, 6, 6, 8, 3, 3, 1, 1, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
+    x = torch.zeros((2, 6, 6, 8), device="cuda"); w = torch.zeros((8, 3, 3, 8), device="cuda")
+    b = torch.zeros((8,), device="cuda"); y = torch.full((2, 6, 6, 8), 7.0, device="cuda")
+    with pytest.raises(m.OwtError) as ei:
+        m.owt_conv_fwd(d, x, w, None, y)                         # OWT_BIAS without a bias pointer
+    assert ei.value.status == m.OWT_EINVAL and "bias" in str(ei.value)
+    with pytest.raises(m.OwtError) as ei:
+        m.owt_conv_bwd_data(d, y, None, w, x)                    # OWT_RELU without y
+    assert ei.value.status == m.OWT_EINVAL
+    with pytest.raises(m.OwtError) as ei:
+        m.owt_conv_fwd(d, x.data_ptr() + 4, w, b, y)             # misaligned
+    assert ei.value.status == m.OWT_EINVAL
+    big = m.conv_desc(16, 192, 13, 13, 384, 3, 3, 1, 1, m.OWT_F32, 0)
+    need = m.owt_conv_workspace_bytes(big, m.OWT_PASS_BWD_FILTER)
+    assert need > 0
+    with pytest.raises(m.OwtError) as ei:
+        m.owt_conv_bwd_filter(big, x, y, None, 1.0, 0.0, w, None, workspace(16))
+    assert ei.value.status == m.OWT_EWORKSPACE
+    torch.cuda.synchronize()
+    assert (y == 7.0).all()
