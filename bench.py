@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of one worker's hot path on one MI355X: the five-layer convolution
+stack, forward + backward, fp32, batch 128 (the per-worker batch of Section 4 of
+the paper), on seeded synthetic images of the ILSVRC crop shape 224x224x3.
+
+A step = conv1..5 forward (bias+ReLU fused, 3 max-pools), then 3 pool-backward,
+5 backward-filter (+bias gradient) and 4 backward-data calls (the first layer's
+input is data, so its dx has no consumer).  Inputs live in HBM before the clock
+starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense MFMA peaks (fp32 matrix, bf16)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="conv_stack",
+                    choices=["conv_stack", "conv_stack_fc", "conv_stack_bf16", "conv_stack_paper"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-images", type=int, default=32)
+    ap.add_argument("--per-call-reps", type=int, default=10)
+    ap.add_argument("--table", action="store_true", help="also print the per-call table to stderr")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (one worker's share of the method); "
+              "--gpus %d is not supported." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import synthetic_inputs as si
+    import paper_1404_5997_amd as owt
+    from paper_1404_5997_amd.stack import ConvStack
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dt = "bf16" if args.workload == "conv_stack_bf16" else "f32"
+    N = 1024 if dt == "bf16" else 128
+    cfg = {"conv_stack": 3, "conv_stack_fc": 4, "conv_stack_bf16": 5, "conv_stack_paper": 3}[args.workload]
+    filters = si.PAPER_FILTERS if args.workload == "conv_stack_paper" else None
+    layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
+    with_fc = args.workload == "conv_stack_fc"
+
+    def rnd(a):
+        if dt != "bf16":
+            return a
+        return torch.from_numpy(a).to(torch.bfloat16).float().numpy()     # input preparation only
+
+    st = ConvStack(N, layers, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
+                   fc_layers=si.FC_LAYERS if with_fc else None, fc_workers=si.FC_WORKERS)
+    x = rnd(si.stack_input(cfg, N))
+    ws, bs = si.stack_params(cfg, filters)
+    ws = [rnd(w) for w in ws]
+    if with_fc:
+        fws, fbs = si.fc_params(cfg)
+        st.load(x, ws, bs, fws, fbs, [si.fc_peer_columns(cfg, i, N) for i in range(2)])
+    else:
+        st.load(x, ws, bs)
+    g = rnd(si.upstream_grad(cfg, 90, tuple(st.top_grad().shape)))
+    st.top_grad().copy_(torch.from_numpy(g).to(st.tdt))
+    torch.cuda.synchronize()
+
+    # ---------------------------------------------------------------- timed region
+    for _ in range(args.warmup):
+        st.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        st.step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    images_per_s = N / (ms_per_step * 1e-3)
+    conv_flops, fc_flops = st.conv_flops(), st.fc_flops()
+    tflops = (conv_flops + fc_flops) / (ms_per_step * 1e-3) / 1e12
+
+    # ------------------------------------------------- per-call durations (HIP events)
+    # Events are recorded on torch's current stream, which is the stream the binding launches on.
+    recs = {}
+
+    def hook(tag, thunk):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); thunk(); b.record()
+        recs.setdefault(tag, []).append((a, b))
+
+    st.hook = hook
+    for _ in range(args.per_call_reps):
+        st.step()
+    torch.cuda.synchronize()
+    st.hook = None
+    per_call = {tag: float(np.mean([a.elapsed_time(b) for a, b in evs])) for tag, evs in recs.items()}   # ms
+
+    # group convolution launches by the kernel variant the planner picked
+    groups = {}
+    for li, e in enumerate(st.L):
+        Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+        fl = 2.0 * Nn * P * Q * K * R * R * C
+        for ps, pname in ((0, "fwd"), (1, "bwd_data"), (2, "bwd_filter")):
+            tag = "conv%d %s" % (li + 1, pname)
+            if tag not in per_call:
+                continue
+            desc = owt.owt_conv_plan_describe(e["desc"], ps).rsplit(" grid", 1)[0]
+            gk = groups.setdefault(desc, dict(ms=0.0, flops=0.0, launches=0, calls=[]))
+            gk["ms"] += per_call[tag]; gk["flops"] += fl; gk["launches"] += 1; gk["calls"].append(tag)
+    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+    achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dom_name, "calls": dom["calls"],
+                "avg_launch_ms": dom["ms"] / dom["launches"],
+                "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
+                "frac": round(achieved / PEAK_TFLOPS[dt], 4), "traffic": None}
+    table = {tag: round(ms, 4) for tag, ms in per_call.items()}
+
+    # ------------------------------------------------------------------ CPU baseline
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n = min(args.cpu_sample_images, N)
+        xs, gs = x[:n], g[:n]
+        t0 = time.perf_counter()
+        acts, cur = [], xs
+        for li, L in enumerate(layers):
+            y = oracle.conv_fwd(cur, ws[li], bs[li], L["stride"], L["pad"], True)
+            rec = dict(x=cur, y=y)
+            cur = y
+            if L["pool"]:
+                cur, rec["am"] = oracle.maxpool_fwd(y, si.POOL_WIN, si.POOL_STRIDE)
+            acts.append(rec)
+        grad = gs if not with_fc else np.zeros_like(cur)
+        for li in range(len(layers) - 1, -1, -1):
+            L, rec = layers[li], acts[li]
+            if L["pool"]:
+                grad = oracle.maxpool_bwd(grad, rec["am"], rec["y"].shape[1:3], si.POOL_WIN, si.POOL_STRIDE)
+            oracle.conv_bwd_filter(rec["x"], grad, (L["R"], L["R"]), L["stride"], L["pad"], y=rec["y"], alpha=1.0 / n)
+            if li > 0:
+                grad = oracle.conv_bwd_data(grad, ws[li], rec["x"].shape[1:3], L["stride"], L["pad"], y=rec["y"])
+        dtc = time.perf_counter() - t0
+        cpu = {"value": round(n / dtc, 3), "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "conv stack fwd+bwd (fp32 in, double accumulate) on %d of the %d images, %.1f s" % (n, N, dtc)}
+
+    out = {
+        "metric": "conv-stack fwd+bwd images/sec at batch 128; TFLOP/s as % MFMA peak",
+        "value": round(images_per_s, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
+        "config": {"workload": {"conv_stack": "config 3: 5-layer conv stack 64/192/384/256/256, fp32, batch 128, 224x224x3, full fwd+bwd",
+                                "conv_stack_fc": "config 4: config-3 stack + FC shard K=8 (512/512/125 columns), fp32, batch 128",
+                                "conv_stack_bf16": "config 5: config-3 stack, bf16 storage / fp32 accumulate, batch 1024",
+                                "conv_stack_paper": "paper filter counts 64/192/384/384/256, fp32, batch 128"}[args.workload],
+                   "batch": N, "conv_gflop_per_step": round(conv_flops / 1e9, 2),
+                   "fc_gflop_per_step": round(fc_flops / 1e9, 2)},
+        "tflops": round(tflops, 3), "frac_of_mfma_peak": round(tflops / PEAK_TFLOPS[dt], 4),
+        "roofline": roofline, "cpu_baseline": cpu, "per_call_ms": table,
+    }
+    if args.table:
+        for tag, ms in sorted(per_call.items(), key=lambda kv: -kv[1]):
+            print("%-20s %8.3f ms" % (tag, ms), file=sys.stderr)
+        for k, v in groups.items():
+            print("%-60s %8.3f ms  %7.2f TFLOP/s" % (k, v["ms"], v["flops"] / v["ms"] / 1e9), file=sys.stderr)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

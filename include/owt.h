@@ -83,6 +83,12 @@ typedef struct {
 size_t owt_conv_workspace_bytes(const owt_conv_desc *d, int pass);
 size_t owt_fc_workspace_bytes(const owt_fc_desc *d, int pass);
 
+/* Diagnostics: writes a one-line description of the kernel variant, tile shape,
+ * split-K factor and grid the planner picks for this pass into buf (NUL
+ * terminated, truncated to buf_bytes).  Returns the untruncated length, or -1
+ * on a bad argument.  Host only. */
+int owt_conv_plan_describe(const owt_conv_desc *d, int pass, char *buf, size_t buf_bytes);
+
 /* Convolution forward (Section 4, forward step 2):
  *   y[n,p,q,k] = act(bias[k] + sum_{r,s,c} x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c] * w[k,r,s,c])
  * taps outside the image count as 0; act = max(0,.) with OWT_RELU, identity

@@ -192,3 +192,7 @@ def round_bf16(a):
     out = np.empty_like(a)
     lib().oracle_round_bf16(_p(a), _p(out), ctypes.c_size_t(a.size))
     return out
+
+
+def num_threads():
+    return int(lib().oracle_num_threads())

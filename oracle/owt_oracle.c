@@ -51,3 +51,7 @@ void oracle_round_bf16(const float *in, float *out, size_t n)
 }
 
 int oracle_abi_version(void) { return 1; }
+
+/* Threads the OpenMP loops above run on. */
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }

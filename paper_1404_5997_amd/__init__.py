@@ -22,7 +22,7 @@ OWT_PASS_FWD, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER = 0, 1, 2
 EXPORTS = (
     "owt_conv_workspace_bytes", "owt_fc_workspace_bytes", "owt_conv_fwd", "owt_conv_bwd_data",
     "owt_conv_bwd_filter", "owt_fc_shard_fwd", "owt_fc_shard_bwd", "owt_maxpool_fwd",
-    "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host",
+    "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe",
 )
 
 
@@ -63,6 +63,7 @@ _lib.owt_maxpool_fwd.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 _lib.owt_maxpool_bwd.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 _lib.owt_last_error.restype = ctypes.c_char_p
 _lib.owt_abi_version.restype = _i
+_lib.owt_conv_plan_describe.argtypes = [_cd, _i, ctypes.c_char_p, _sz]
 
 
 def _ptr(t):
@@ -100,6 +101,14 @@ def owt_last_error():
 
 def owt_abi_version():
     return _lib.owt_abi_version()
+
+
+def owt_conv_plan_describe(desc, pass_):
+    buf = ctypes.create_string_buffer(256)
+    n = _lib.owt_conv_plan_describe(ctypes.byref(desc), pass_, buf, ctypes.c_size_t(256))
+    if n < 0:
+        raise OwtError(OWT_EINVAL, owt_last_error())
+    return buf.value.decode()
 
 
 def owt_selftest_host():

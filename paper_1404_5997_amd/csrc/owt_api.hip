@@ -41,9 +41,14 @@ Plan plan_gemm(long M, long Ncols, long Kd, bool vec_ok, bool want_dbias)
         const TileInfo &ti = kTiles[t];
         const long BM = 64 * ti.WM, BN = 64 * ti.WN;
         const long tm = cdiv(M, BM), tn = cdiv(Ncols, BN), ksteps = cdiv(Kd, ti.BK);
-        for (int s : kSplits) {
-            if (force_split > 0 && s != force_split && !(s == 1 && force_split > ksteps)) continue;
-            if (s > 1 && ksteps / s < 4) break;
+        for (int s0 : kSplits) {
+            long s = s0;
+            if (force_split > 0) {           // tuning/test override: take it as given, capped by the steps there are
+                if (s0 != 1) break;
+                s = force_split < ksteps ? force_split : ksteps;
+            } else if (s > 1 && ksteps / s < 4) {
+                break;
+            }
             const long per = cdiv(ksteps, s);
             const long splits = cdiv(ksteps, per);        // drop empty trailing splits
             const long wgs = tm * tn * splits;
@@ -199,6 +204,20 @@ size_t owt_conv_workspace_bytes(const owt_conv_desc *d, int pass)
     if (check_conv(d, g) != OWT_OK) return (size_t)-1;
     const PassDims dm = conv_dims(g, pass);
     return plan_gemm(dm.M, dm.Ncols, dm.Kd, dm.va && dm.vb, pass == OWT_PASS_BWD_FILTER).total_bytes();
+}
+
+int owt_conv_plan_describe(const owt_conv_desc *d, int pass, char *buf, size_t buf_bytes)
+{
+    Geom g;
+    if (pass < 0 || pass > 2 || !buf || buf_bytes == 0) { fail(OWT_EINVAL, "bad pass or buffer"); return -1; }
+    if (check_conv(d, g) != OWT_OK) return -1;
+    const PassDims dm = conv_dims(g, pass);
+    const Plan pl = plan_gemm(dm.M, dm.Ncols, dm.Kd, dm.va && dm.vb, pass == OWT_PASS_BWD_FILTER);
+    static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
+    const TileInfo &ti = kTiles[pl.tile];
+    return snprintf(buf, buf_bytes, "igemm %s %s tile%dx%dx%d vec%d/%d splitk%d grid%dx%d", pn[pass],
+                    d->dtype == OWT_BF16 ? "bf16" : "f32", 64 * ti.WM, 64 * ti.WN, ti.BK, dm.va ? 4 : 1,
+                    dm.vb ? 4 : 1, pl.splits, pl.tiles_m * pl.tiles_n, pl.splits);
 }
 
 owt_status owt_conv_fwd(const owt_conv_desc *d, const void *x, const void *w, const float *bias,

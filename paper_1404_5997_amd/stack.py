@@ -1,0 +1,175 @@
+"""Sequencing of one worker's step through libowt: the five convolution layers
+(+ max-pools) forward and backward, and optionally the worker's fully-connected
+column shards (Section 4 of the paper, forward steps 1-3 and backward steps 1-2;
+model of Section 5).
+
+This file holds buffers and call order only; every arithmetic step runs in the
+library's kernels.  torch provides device memory.  The one data movement done
+here, copying this worker's 512 hidden columns into the [N, 4096] input of the
+next fully-connected layer next to the columns the other workers would have
+sent, stands in for the exchange between workers, which is outside a one-GPU
+build.
+"""
+import torch
+
+from . import (OWT_BF16, OWT_BIAS, OWT_F32, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER, OWT_PASS_FWD, OWT_RELU,
+               conv_desc, fc_desc, owt_conv_bwd_data, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
+               owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_maxpool_bwd, owt_maxpool_fwd)
+
+
+class ConvStack:
+    """layers: sequence of dicts K, R, stride, pad, pool (bool); input_hwc: (H, W, C)."""
+
+    def __init__(self, N, layers, input_hwc, pool=(3, 2), dtype="f32", fc_layers=None, fc_workers=8,
+                 skip_first_dx=True):
+        self.N, self.dt = N, dtype
+        self.code = OWT_BF16 if dtype == "bf16" else OWT_F32
+        self.tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        self.win, self.pst = pool
+        self.skip_first_dx = skip_first_dx
+        dev = "cuda"
+        H, W, C = input_hwc
+        self.x = torch.empty((N, H, W, C), device=dev, dtype=self.tdt)
+        self.L = []
+        ws_bytes = 16
+        for spec in layers:
+            K, R, st, pad = spec["K"], spec["R"], spec["stride"], spec["pad"]
+            d = conv_desc(N, C, H, W, K, R, R, st, pad, self.code, OWT_BIAS | OWT_RELU)
+            P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - R) // st + 1
+            e = dict(desc=d, geom=(N, C, H, W, K, R, st, pad, P, Q), pool=spec["pool"],
+                     w=torch.empty((K, R, R, C), device=dev, dtype=self.tdt),
+                     b=torch.empty((K,), device=dev, dtype=torch.float32),
+                     y=torch.empty((N, P, Q, K), device=dev, dtype=self.tdt),
+                     dy=torch.empty((N, P, Q, K), device=dev, dtype=self.tdt),
+                     dw=torch.empty((K, R, R, C), device=dev, dtype=torch.float32),
+                     db=torch.empty((K,), device=dev, dtype=torch.float32))
+            for p in (OWT_PASS_FWD, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER):
+                ws_bytes = max(ws_bytes, owt_conv_workspace_bytes(d, p))
+            H, W, C = P, Q, K
+            if spec["pool"]:
+                PP, QQ = (H - self.win) // self.pst + 1, (W - self.win) // self.pst + 1
+                e["a"] = torch.empty((N, PP, QQ, K), device=dev, dtype=self.tdt)
+                e["am"] = torch.empty((N, PP, QQ, K), device=dev, dtype=torch.uint8)
+                e["da"] = torch.empty((N, PP, QQ, K), device=dev, dtype=self.tdt)
+                H, W = PP, QQ
+            self.L.append(e)
+        self.out_shape = (N, H, W, C)
+        # the gradient w.r.t. a layer's output lives in that layer's dy (no pool) or da (pool)
+        self.F = []
+        if fc_layers:
+            I0 = H * W * C
+            for i, spec in enumerate(fc_layers):
+                assert spec["I"] == (I0 if i == 0 else fc_layers[i - 1]["O_total"])
+                flags = OWT_BIAS | (OWT_RELU if spec["relu"] else 0)
+                d = fc_desc(N, spec["I"], spec["O_total"], fc_workers, 0, self.code, flags)
+                O = spec["O_total"] // fc_workers
+                f = dict(desc=d, I=spec["I"], O=O, O_total=spec["O_total"], relu=spec["relu"],
+                         w=torch.empty((O, spec["I"]), device=dev, dtype=self.tdt),
+                         b=torch.empty((O,), device=dev, dtype=torch.float32),
+                         y=torch.empty((N, O), device=dev, dtype=self.tdt),
+                         dy=torch.empty((N, O), device=dev, dtype=self.tdt),
+                         dx=torch.empty((N, spec["I"]), device=dev, dtype=self.tdt),
+                         dw=torch.empty((O, spec["I"]), device=dev, dtype=torch.float32),
+                         db=torch.empty((O,), device=dev, dtype=torch.float32))
+                if i > 0:   # input assembled from own columns + the peers' columns
+                    f["x"] = torch.zeros((N, spec["I"]), device=dev, dtype=self.tdt)
+                for p in (OWT_PASS_FWD, OWT_PASS_BWD_DATA):
+                    ws_bytes = max(ws_bytes, owt_fc_workspace_bytes(d, p))
+                self.F.append(f)
+        if self.F:   # the first dense layer's dx_partial IS the gradient of the last pooled map
+            e = self.L[-1]
+            self.F[0]["dx"] = (e["da"] if e["pool"] else e["dy"]).view(N, -1)
+        self.ws = torch.empty((ws_bytes,), device=dev, dtype=torch.uint8)
+        self.hook = None
+        self.alpha = 1.0 / N      # batch-mean weight gradient (update rule of Section 5)
+        self.beta = 0.0
+
+    # ------------------------------------------------------------------ setup
+    def load(self, x, ws, bs, fc_ws=None, fc_bs=None, fc_peers=None):
+        """Host numpy arrays (already bf16-representable for bf16 stacks) -> device buffers."""
+        self.x.copy_(torch.from_numpy(x).to(self.tdt))
+        for e, w, b in zip(self.L, ws, bs):
+            e["w"].copy_(torch.from_numpy(w).to(self.tdt)); e["b"].copy_(torch.from_numpy(b))
+        if self.F:
+            for f, w, b in zip(self.F, fc_ws, fc_bs):
+                f["w"].copy_(torch.from_numpy(w).to(self.tdt)); f["b"].copy_(torch.from_numpy(b))
+            for i, f in enumerate(self.F[1:], start=1):
+                own = self.F[i - 1]["O"]
+                f["x"][:, own:].copy_(torch.from_numpy(fc_peers[i - 1]).to(self.tdt))
+
+    def top_grad(self):
+        """Buffer the caller fills with the gradient w.r.t. the stack output."""
+        if self.F:
+            return self.F[-1]["dy"]
+        e = self.L[-1]
+        return e["da"] if e["pool"] else e["dy"]
+
+    # --------------------------------------------------------------- one step
+    def _run(self, tag, fn, *args):
+        """Every library call of a step goes through here; `self.hook`, when set, is called as
+        hook(tag, thunk) and must invoke the thunk once (used to bracket calls with events)."""
+        if self.hook is None:
+            fn(*args)
+        else:
+            self.hook(tag, lambda: fn(*args))
+
+    def forward(self):
+        cur = self.x
+        for li, e in enumerate(self.L):
+            N, C, H, W, K, R, st, pad, P, Q = e["geom"]
+            e["x"] = cur
+            self._run("conv%d fwd" % (li + 1), owt_conv_fwd, e["desc"], cur, e["w"], e["b"], e["y"], self.ws)
+            cur = e["y"]
+            if e["pool"]:
+                self._run("pool%d fwd" % (li + 1), owt_maxpool_fwd, N, P, Q, K, self.win, self.pst, self.code, e["y"], e["a"], e["am"])
+                cur = e["a"]
+        for i, f in enumerate(self.F):
+            if i == 0:
+                f["x"] = cur.view(self.N, -1)
+            else:
+                prev = self.F[i - 1]
+                f["x"][:, :prev["O"]].copy_(prev["y"])        # own columns (rank 0) beside the peers'
+            self._run("fc%d fwd" % (i + 1), owt_fc_shard_fwd, f["desc"], f["x"], f["w"], f["b"], f["y"], self.ws)
+            cur = f["y"]
+        return cur
+
+    def backward(self):
+        for i in range(len(self.F) - 1, -1, -1):
+            f = self.F[i]
+            self._run("fc%d bwd" % (i + 1), owt_fc_shard_bwd, f["desc"], f["x"], f["w"],
+                      f["y"] if f["relu"] else None, f["dy"], self.alpha, self.beta, f["dx"], f["dw"], f["db"], self.ws)
+            if i > 0:   # the slice of dx_partial that belongs to this worker's own columns
+                self.F[i - 1]["dy"].copy_(f["dx"][:, :self.F[i - 1]["O"]])
+        for li in range(len(self.L) - 1, -1, -1):
+            e = self.L[li]
+            N, C, H, W, K, R, st, pad, P, Q = e["geom"]
+            if e["pool"]:
+                self._run("pool%d bwd" % (li + 1), owt_maxpool_bwd, N, P, Q, K, self.win, self.pst, self.code, e["da"], e["am"], e["dy"])
+            self._run("conv%d bwd_filter" % (li + 1), owt_conv_bwd_filter, e["desc"], e["x"], e["dy"], e["y"], self.alpha, self.beta,
+                      e["dw"], e["db"], self.ws)
+            if li > 0:
+                prev = self.L[li - 1]
+                self._run("conv%d bwd_data" % (li + 1), owt_conv_bwd_data, e["desc"], e["dy"], e["y"], e["w"],
+                          prev["da"] if prev["pool"] else prev["dy"], self.ws)
+            elif not self.skip_first_dx:
+                if "dx0" not in e:
+                    e["dx0"] = torch.empty_like(self.x)
+                self._run("conv1 bwd_data", owt_conv_bwd_data, e["desc"], e["dy"], e["y"], e["w"], e["dx0"], self.ws)
+
+    def step(self):
+        self.forward()
+        self.backward()
+
+    # ----------------------------------------------------------- work counters
+    def conv_flops(self):
+        """2*MAC of the dense definition per step: fwd + bwd-filter for every layer, bwd-data for all
+        but the first (its input is data) unless skip_first_dx is off."""
+        total = 0
+        for li, e in enumerate(self.L):
+            N, C, H, W, K, R, st, pad, P, Q = e["geom"]
+            one = 2 * N * P * Q * K * R * R * C
+            total += one * (3 if (li > 0 or not self.skip_first_dx) else 2)
+        return total
+
+    def fc_flops(self):
+        return sum(2 * self.N * f["I"] * f["O"] * 3 for f in self.F)

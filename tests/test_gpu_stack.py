@@ -1,0 +1,177 @@
+"""GPU parity of the chained hot path at the benchmark's full sizes and launch
+configuration: the five-layer convolution stack (configs 3 and 5) and the stack
+plus fully-connected shards (config 4).
+
+The whole batch runs on the GPU.  The oracle cannot redo 485 GFLOP in a test, so:
+ * forward: the oracle runs free on a few images (convolution, ReLU and pooling
+   act per image) and every layer's output of those images is compared;
+ * pooling: the GPU's pooled maxima and arg-max must equal, bit for bit, the
+   oracle's pooling of the GPU's own convolution output (all images);
+ * backward-data: the oracle back-propagates the same upstream gradient through
+   the same images, using the GPU's forward outputs as ReLU masks and the GPU's
+   arg-max (both just shown valid), and every layer's dx is compared.  ReLU and
+   arg-max are not smooth, so an element that is +1e-9 on one side and 0 on the
+   other would otherwise move gradients by far more than rounding; feeding both
+   sides the same mask makes every backward call a pure function of its inputs;
+ * backward-filter: sampled entries of every layer's dw (a sum over the WHOLE
+   batch) are recomputed one by one by the oracle from the GPU's full-batch
+   inputs of that call; db likewise (all entries).
+"""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+import synthetic_inputs as si
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from gpu_util import TOL, assert_close, rel_err, to_host  # noqa: E402
+
+
+def say(*a):
+    print(*a)
+    sys.stdout.flush()
+
+
+def build_stack(config, N, dt, with_fc=False):
+    from paper_1404_5997_amd.stack import ConvStack
+    r = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
+    x = r(si.stack_input(config, N))
+    ws, bs = si.stack_params(config)
+    ws = [r(w) for w in ws]
+    st = ConvStack(N, si.STACK_LAYERS, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
+                   fc_layers=si.FC_LAYERS if with_fc else None, fc_workers=si.FC_WORKERS)
+    fc = None
+    if with_fc:
+        fws, fbs = si.fc_params(config)
+        fws = [r(w) for w in fws]
+        peers = [r(si.fc_peer_columns(config, i, N)) for i in range(2)]
+        st.load(x, ws, bs, fws, fbs, peers)
+        fc = (fws, fbs, peers)
+    else:
+        st.load(x, ws, bs)
+    g = r(si.upstream_grad(config, 90, tuple(st.top_grad().shape)))
+    st.top_grad().copy_(torch.from_numpy(g).to(st.tdt))
+    return st, x, ws, bs, g, fc
+
+
+def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, n_sub, n_dw_samples=96):
+    """dtop_pooled: host copy of the gradient w.r.t. the last pooled map, as the GPU backward consumed it."""
+    N = st.N
+    rnd = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
+    sub = slice(0, n_sub)
+    win, pst = si.POOL_WIN, si.POOL_STRIDE
+
+    # ---- forward, free-running oracle on the first n_sub images
+    cur = x[sub]
+    flips = []
+    for li, (e, spec) in enumerate(zip(st.L, si.STACK_LAYERS)):
+        y_ref = rnd(oracle.conv_fwd(cur, ws[li], bs[li], spec["stride"], spec["pad"], True))
+        y_gpu = to_host(e["y"][sub])
+        err = assert_close(y_gpu, y_ref, dt, "conv%d fwd" % (li + 1))
+        flips.append(int(np.sum((y_gpu > 0) != (y_ref > 0))))
+        cur = y_ref
+        if spec["pool"]:
+            a_ref, _ = oracle.maxpool_fwd(y_ref, win, pst)
+            assert_close(to_host(e["a"][sub]), a_ref, dt, "pool%d fwd" % (li + 1))
+            cur = a_ref
+        say("  conv%d fwd rel err %.2e, ReLU mask disagreements %d of %d" % (li + 1, err, flips[-1], y_ref.size))
+
+    # ---- pooling of the GPU's own conv output: exact, all images
+    for li, e in enumerate(st.L):
+        if not e["pool"]:
+            continue
+        y_gpu = to_host(e["y"])
+        a_ref, am_ref = oracle.maxpool_fwd(y_gpu, win, pst)
+        np.testing.assert_array_equal(to_host(e["a"]), a_ref)
+        np.testing.assert_array_equal(e["am"].cpu().numpy(), am_ref)
+        del y_gpu, a_ref, am_ref
+    say("  pooled maxima and arg-max exact on all images")
+
+    # ---- backward-data chain on the first n_sub images, GPU masks / arg-max as inputs
+    g = dtop_pooled[sub]
+    for li in range(len(st.L) - 1, -1, -1):
+        e, spec = st.L[li], si.STACK_LAYERS[li]
+        Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+        if spec["pool"]:
+            g = rnd(oracle.maxpool_bwd(g, e["am"][sub].cpu().numpy(), (P, Q), win, pst))
+            assert_close(to_host(e["dy"][sub]), g, dt, "pool%d bwd" % (li + 1))
+        if li == 0:
+            break
+        y_mask = to_host(e["y"][sub])
+        g = rnd(oracle.conv_bwd_data(g, ws[li], (H, W), stv, pad, y=y_mask))
+        prev = st.L[li - 1]
+        got = to_host((prev["da"] if prev["pool"] else prev["dy"])[sub])
+        err = assert_close(got, g, dt, "conv%d bwd_data" % (li + 1))
+        say("  conv%d bwd_data rel err %.2e" % (li + 1, err))
+
+    # ---- backward-filter: sampled dw entries and all of db from the GPU's full-batch call inputs
+    rs = np.random.default_rng(123)
+    for li, e in enumerate(st.L):
+        Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+        xin, dyin, yin = to_host(e["x"]), to_host(e["dy"]), to_host(e["y"])
+        idx = np.stack([rs.integers(0, K, n_dw_samples), rs.integers(0, R, n_dw_samples),
+                        rs.integers(0, R, n_dw_samples), rs.integers(0, C, n_dw_samples)], axis=1).astype(np.int32)
+        idx[0] = (0, 0, 0, 0); idx[1] = (K - 1, R - 1, R - 1, C - 1)
+        ref = oracle.conv_bwd_filter_at(xin, dyin, idx, (R, R), stv, pad, y=yin).astype(np.float64) * st.alpha
+        dw = e["dw"].cpu().numpy()
+        got = dw[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+        scale = np.max(np.abs(dw))          # the tensor's max norm (the sample need not contain it)
+        err = float(np.max(np.abs(got - ref)) / scale)
+        assert np.isfinite(dw).all() and err <= TOL["f32"], "conv%d dw: %.3e" % (li + 1, err)
+        # db[k] = alpha * sum dz: the dense-layer oracle on a [N*P*Q, K] matrix with a zero input column
+        rows = Nn * P * Q
+        _, _, db_ref = oracle.fc_bwd(np.zeros((rows, 1), np.float32), np.zeros((K, 1), np.float32),
+                                     dyin.reshape(rows, K), y=yin.reshape(rows, K), alpha=st.alpha, want_dx=False)
+        errb = assert_close(e["db"].cpu().numpy(), db_ref, "f32", "conv%d db" % (li + 1))
+        say("  conv%d dw (sampled %d) rel err %.2e, db rel err %.2e" % (li + 1, n_dw_samples, err, errb))
+        del xin, dyin, yin
+    return flips
+
+
+def test_config3_conv_stack_fp32_batch128():
+    st, x, ws, bs, g, _ = build_stack(3, 128, "f32")
+    st.step()
+    torch.cuda.synchronize()
+    say("config 3: stack ran, output", st.out_shape)
+    assert st.out_shape == (128, 6, 6, 256)
+    flips = check_conv_stack(st, x, ws, bs, g, "f32", n_sub=3)
+    assert sum(flips) <= 50
+
+
+def test_config5_conv_stack_bf16_batch1024():
+    st, x, ws, bs, g, _ = build_stack(5, 1024, "bf16")
+    st.step()
+    torch.cuda.synchronize()
+    say("config 5: stack ran, output", st.out_shape)
+    check_conv_stack(st, x, ws, bs, g, "bf16", n_sub=2, n_dw_samples=48)
+
+
+def test_config4_stack_plus_fc_shard_fp32():
+    st, x, ws, bs, g, (fws, fbs, peers) = build_stack(4, 128, "f32", with_fc=True)
+    st.step()
+    torch.cuda.synchronize()
+    # every dense call against the oracle on the GPU's inputs of that call (full batch: they are small)
+    for i, (f, spec) in enumerate(zip(st.F, si.FC_LAYERS)):
+        xin = to_host(f["x"])
+        y_ref = oracle.fc_fwd(xin, fws[i], fbs[i], spec["relu"])
+        e1 = assert_close(to_host(f["y"]), y_ref, "f32", "fc%d fwd" % (i + 1))
+        dyin = to_host(f["dy"])
+        dx_ref, dw_ref, db_ref = oracle.fc_bwd(xin, fws[i], dyin, y=to_host(f["y"]) if spec["relu"] else None,
+                                               alpha=st.alpha)
+        e2 = assert_close(to_host(f["dx"]), dx_ref, "f32", "fc%d dx_partial" % (i + 1))
+        e3 = assert_close(to_host(f["dw"]), dw_ref, "f32", "fc%d dw" % (i + 1))
+        e4 = assert_close(to_host(f["db"]), db_ref, "f32", "fc%d db" % (i + 1))
+        say("  fc%d rel err fwd %.2e dx %.2e dw %.2e db %.2e" % (i + 1, e1, e2, e3, e4))
+        if i > 0:   # the hand-over between layers: own columns in front, the peers' columns behind
+            own = st.F[i - 1]["O"]
+            np.testing.assert_array_equal(xin[:, :own], to_host(st.F[i - 1]["y"]))
+            np.testing.assert_array_equal(xin[:, own:], peers[i - 1])
+            np.testing.assert_array_equal(to_host(st.F[i - 1]["dy"]), to_host(f["dx"])[:, :own])
+    # free-running forward of the dense part on the oracle's own conv features for a few images
+    e = st.L[-1]
+    pooled_dgrad = to_host(e["da"])           # = fc1's dx_partial, reshaped
+    check_conv_stack(st, x, ws, bs, pooled_dgrad, "f32", n_sub=2, n_dw_samples=32)
