@@ -33,6 +33,7 @@ def main():
     ap.add_argument("--cpu-sample-images", type=int, default=32)
     ap.add_argument("--per-call-reps", type=int, default=10)
     ap.add_argument("--table", action="store_true", help="also print the per-call table to stderr")
+    ap.add_argument("--no-autotune", action="store_true", help="let the cost model pick kernel variants")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one worker's share of the method); "
@@ -71,6 +72,8 @@ def main():
         st.load(x, ws, bs)
     g = rnd(si.upstream_grad(cfg, 90, tuple(st.top_grad().shape)))
     st.top_grad().copy_(torch.from_numpy(g).to(st.tdt))
+    if not args.no_autotune:
+        st.autotune()      # set-up, outside the timed region: the library times its variants per layer
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- timed region

@@ -116,6 +116,21 @@ owt_status owt_conv_bwd_filter(const owt_conv_desc *d, const void *x, const void
                                const void *y_or_null, float alpha, float beta, float *dw,
                                float *dbias_or_null, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* Optional tuning.  Runs every kernel variant the planner knows for this pass
+ * on the caller's buffers (three timed repetitions each, HIP events on
+ * hip_stream), and remembers the fastest: later owt_conv_* calls in this
+ * process with an identical descriptor use it.  Blocks until the timing is
+ * done.  Buffers are those of the pass itself (others may be NULL):
+ *   OWT_PASS_FWD        reads x, w, bias              writes y
+ *   OWT_PASS_BWD_DATA   reads dy, y (mask), w         writes dx
+ *   OWT_PASS_BWD_FILTER reads x, dy, y (mask)         writes dw, dbias (alpha 1, beta 0)
+ * ws must hold owt_conv_workspace_bytes(d, pass).  Without this call a cost
+ * model picks the variant; results are identical up to summation order.
+ * For callers that can afford a few milliseconds of set-up per layer. */
+owt_status owt_conv_autotune(const owt_conv_desc *d, int pass, const void *x, const void *w, const float *bias,
+                             void *y, const void *dy, void *dx, float *dw, float *dbias_or_null, void *ws,
+                             size_t ws_bytes, void *hip_stream);
+
 /* Fully-connected column shard forward (Section 4, forward step 3):
  *   y[n,o] = act(bias[o] + sum_i x[n,i] * w[o,i]),  o over this worker's O_local columns.
  * x [N,I], w [O_local,I], bias [O_local] fp32, y [N,O_local] (written). */

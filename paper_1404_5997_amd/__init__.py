@@ -22,7 +22,7 @@ OWT_PASS_FWD, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER = 0, 1, 2
 EXPORTS = (
     "owt_conv_workspace_bytes", "owt_fc_workspace_bytes", "owt_conv_fwd", "owt_conv_bwd_data",
     "owt_conv_bwd_filter", "owt_fc_shard_fwd", "owt_fc_shard_bwd", "owt_maxpool_fwd",
-    "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe",
+    "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe", "owt_conv_autotune",
 )
 
 
@@ -57,6 +57,7 @@ _lib.owt_fc_workspace_bytes.argtypes = [_fd, _i]
 _lib.owt_conv_fwd.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_conv_bwd_data.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_conv_bwd_filter.argtypes = [_cd, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _sz, _vp]
+_lib.owt_conv_autotune.argtypes = [_cd, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_fwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_bwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_maxpool_fwd.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
@@ -154,6 +155,12 @@ def owt_conv_bwd_filter(desc, x, dy, y_or_null, alpha, beta, dw, dbias_or_null, 
     p, n = _ws(ws)
     _check(_lib.owt_conv_bwd_filter(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(y_or_null), alpha, beta,
                                     _ptr(dw), _ptr(dbias_or_null), p, n, _stream(stream)))
+
+
+def owt_conv_autotune(desc, pass_, x, w, bias, y, dy, dx, dw, dbias_or_null, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.owt_conv_autotune(ctypes.byref(desc), pass_, _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(dy), _ptr(dx),
+                                  _ptr(dw), _ptr(dbias_or_null), p, n, _stream(stream)))
 
 
 def owt_fc_shard_fwd(desc, x, w, bias, y, ws=None, stream=None):

@@ -24,6 +24,10 @@ def _units():
         for bf in (0, 1):
             units.append(("igemm_%s_%s.o" % (pname, "bf16" if bf else "f32"), "igemm_inst.hip",
                           ["-DOWT_INST_PASS=%d" % ps, "-DOWT_INST_BF16=%d" % bf]))
+    for ps, pname in ((0, "fwd"), (1, "data")):
+        for bf in (0, 1):
+            units.append(("dconv_%s_%s.o" % (pname, "bf16" if bf else "f32"), "dconv_inst.hip",
+                          ["-DOWT_INST_PASS=%d" % ps, "-DOWT_INST_BF16=%d" % bf]))
     return units
 
 

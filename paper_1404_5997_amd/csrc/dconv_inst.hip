@@ -1,0 +1,63 @@
+// Instantiations of the panel-resident stride-1 kernel for one (pass, storage type) pair.
+// Built four times: -DOWT_INST_PASS={0,1} -DOWT_INST_BF16={0,1}.
+#include "dconv.hpp"
+#include "owt_host.hpp"
+
+#ifndef OWT_INST_PASS
+#error "define OWT_INST_PASS (0 fwd, 1 bwd-data)"
+#endif
+#ifndef OWT_INST_BF16
+#error "define OWT_INST_BF16 (0 fp32 storage, 1 bf16 storage)"
+#endif
+
+namespace owt {
+
+#if OWT_INST_BF16
+typedef bf16_t TT;
+#define OWT_SFX(n) n##_bf16
+#else
+typedef float TT;
+#define OWT_SFX(n) n##_f32
+#endif
+
+#if OWT_INST_PASS == 0
+typedef EpiFwd<TT> OE;
+constexpr bool kBwd = false;
+#define OWT_FN OWT_SFX(owt_launch_dconv_fwd)
+#else
+typedef EpiData<TT> OE;
+constexpr bool kBwd = true;
+#define OWT_FN OWT_SFX(owt_launch_dconv_data)
+#endif
+
+template <int WM, int WN, int PR, int BK>
+static hipError_t go(const GemmParams &p, hipStream_t s)
+{
+    const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
+    hipLaunchKernelGGL((dconv_kernel<TT, OE, kBwd, WM, WN, PR, BK>), grid, dim3(64 * WM * WN), 0, s, p);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && p.splits > 1) {
+        const size_t total = (size_t)p.M * p.Ncols;
+        int blocks = (int)((total + 255) / 256);
+        if (blocks > 2048) blocks = 2048;
+        hipLaunchKernelGGL((splitk_reduce_kernel<OE>), dim3(blocks), dim3(256), 0, s, p);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+hipError_t OWT_FN(int tile, int pr, const GemmParams &p, hipStream_t s)
+{
+    // 128x128: 32-channel chunks; 128x64 (two wavefronts): 16-channel chunks keep LDS small
+    // enough for five work-groups per CU
+    if (tile == TILE_128x128) {
+        if (pr <= 160) return go<2, 2, 160, 32>(p, s);
+        if (pr <= 256) return go<2, 2, 256, 32>(p, s);
+    } else if (tile == TILE_128x64) {
+        if (pr <= 160) return go<2, 1, 160, 16>(p, s);
+        if (pr <= 256) return go<2, 1, 256, 16>(p, s);
+    }
+    return hipErrorInvalidValue;
+}
+
+}  // namespace owt

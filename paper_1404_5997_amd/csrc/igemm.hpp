@@ -272,7 +272,7 @@ template <class Acc, int VEC, int ROWS, int BK, int NT> struct TileLoader {
     {
         quad = tid % QUADS;
         line0 = tid / QUADS;
-        if (KMAJOR) {
+        if constexpr (KMAJOR) {
 #pragma unroll
             for (int i = 0; i < NPASS; i++) fx[i][0] = Acc::fix(p, origin + line0 + i * RPP);
         } else {
@@ -303,7 +303,7 @@ template <class Acc, int VEC, int ROWS, int BK, int NT> struct TileLoader {
     // global -> registers for the BK step starting at reduction index k0
     __device__ __forceinline__ void load(const GemmParams &p, const T *src, int k0)
     {
-        if (KMAJOR) {
+        if constexpr (KMAJOR) {
             typename Acc::Red rd[NV];
 #pragma unroll
             for (int j = 0; j < NV; j++) rd[j] = Acc::red(p, k0 + quad * 4 + j);
@@ -349,9 +349,57 @@ template <class Acc, int VEC, int ROWS, int BK, int NT> struct TileLoader {
     }
 };
 
+// ------------------------------------------------------------------ epilogue
+// Stores one wavefront's 64 x 64 block.  Accumulator register r of lane (li, lh) is
+// row slot 8*(r/4) + 4*lh + r%4, column slot li of its 32 x 32 block; a K-major operand
+// maps block b, slot t to index 32*b + t, an MN-major one to 2*t + b.
+template <class Epi, bool AKM, bool BKM>
+__device__ __forceinline__ void tile_epilogue(const GemmParams &p, const float16v (&acc)[2][2], int row0,
+                                              int col0, int li, int lh, int split)
+{
+    typedef typename Epi::TOut TOut;
+    const bool part = p.splits > 1;
+    float *pout = part ? p.partial + (size_t)split * p.M * p.Ncols : nullptr;
+    TOut *out = (TOut *)p.out;
+#pragma unroll
+    for (int bm = 0; bm < 2; bm++) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int rho = 8 * (r / 4) + 4 * lh + (r % 4);
+            const int row = row0 + (AKM ? bm * 32 + rho : 2 * rho + bm);
+            if (row >= p.M) continue;
+            if (BKM) {
+#pragma unroll
+                for (int bn = 0; bn < 2; bn++) {
+                    const int col = col0 + bn * 32 + li;
+                    if (col >= p.Ncols) continue;
+                    const size_t o = (size_t)row * p.Ncols + col;
+                    if (part) pout[o] = acc[bm][bn][r];
+                    else store1(out, o, Epi::op(p, row, col, acc[bm][bn][r]));
+                }
+            } else {
+                const int col = col0 + 2 * li;
+                const size_t o = (size_t)row * p.Ncols + col;
+                const float v0 = acc[bm][0][r], v1 = acc[bm][1][r];
+                if (col + 1 < p.Ncols && (p.Ncols & 1) == 0) {
+                    if (part) *(float2 *)(pout + o) = make_float2(v0, v1);
+                    else store2(out, o, Epi::op(p, row, col, v0), Epi::op(p, row, col + 1, v1));
+                } else {
+                    if (col < p.Ncols) {
+                        if (part) pout[o] = v0; else store1(out, o, Epi::op(p, row, col, v0));
+                    }
+                    if (col + 1 < p.Ncols) {
+                        if (part) pout[o + 1] = v1; else store1(out, o + 1, Epi::op(p, row, col + 1, v1));
+                    }
+                }
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------- kernel
 template <class A, class B, class Epi, int VA, int VB, int WM, int WN, int BK>
-__global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const GemmParams p)
+__global__ void __launch_bounds__(64 * WM * WN, 2) igemm_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WM * WN, BM = 64 * WM, BN = 64 * WN;
     typedef TileLoader<A, VA, BM, BK, NT> LA;
@@ -462,46 +510,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const GemmParams p)
         cur ^= 1;
     }
 
-    // ---- epilogue: accumulator register r of lane (li, lh) is row slot
-    // 8*(r/4) + 4*lh + r%4, column slot li of its 32 x 32 block.
-    typedef typename Epi::TOut TOut;
-    const bool part = p.splits > 1;
-    float *pout = part ? p.partial + (size_t)split * p.M * p.Ncols : nullptr;
-    TOut *out = (TOut *)p.out;
-#pragma unroll
-    for (int bm = 0; bm < 2; bm++) {
-#pragma unroll
-        for (int r = 0; r < 16; r++) {
-            const int rho = 8 * (r / 4) + 4 * lh + (r % 4);
-            const int row = m0 + wm0 + (A::KMAJOR ? bm * 32 + rho : 2 * rho + bm);
-            if (row >= p.M) continue;
-            if (B::KMAJOR) {
-#pragma unroll
-                for (int bn = 0; bn < 2; bn++) {
-                    const int col = n0 + wn0 + bn * 32 + li;
-                    if (col >= p.Ncols) continue;
-                    const size_t o = (size_t)row * p.Ncols + col;
-                    if (part) pout[o] = acc[bm][bn][r];
-                    else store1(out, o, Epi::op(p, row, col, acc[bm][bn][r]));
-                }
-            } else {
-                const int col = n0 + wn0 + 2 * li;
-                const size_t o = (size_t)row * p.Ncols + col;
-                const float v0 = acc[bm][0][r], v1 = acc[bm][1][r];
-                if (col + 1 < p.Ncols && (p.Ncols & 1) == 0) {
-                    if (part) *(float2 *)(pout + o) = make_float2(v0, v1);
-                    else store2(out, o, Epi::op(p, row, col, v0), Epi::op(p, row, col + 1, v1));
-                } else {
-                    if (col < p.Ncols) {
-                        if (part) pout[o] = v0; else store1(out, o, Epi::op(p, row, col, v0));
-                    }
-                    if (col + 1 < p.Ncols) {
-                        if (part) pout[o + 1] = v1; else store1(out, o + 1, Epi::op(p, row, col + 1, v1));
-                    }
-                }
-            }
-        }
-    }
+    tile_epilogue<Epi, A::KMAJOR, B::KMAJOR>(p, acc, m0 + wm0, n0 + wn0, li, lh, split);
 
     if (Epi::DBIAS) {
         // Column sums of the dz tile: threads sharing a quad add up through LDS.
@@ -514,7 +523,7 @@ __global__ void __launch_bounds__(64 * WM * WN) igemm_kernel(const GemmParams p)
                 float s = 0.f;
                 for (int j = 0; j < G; j++) s += red[j * BM + tid];
                 const int k = m0 + tid;
-                if (part) p.dbias_partial[(size_t)split * p.M + k] = s;
+                if (p.splits > 1) p.dbias_partial[(size_t)split * p.M + k] = s;
                 else p.dbias[k] = p.alpha * s + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);
             }
         }

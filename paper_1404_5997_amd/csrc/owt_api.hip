@@ -1,4 +1,9 @@
-// C ABI entry points of libowt: descriptor checks, planning, launches.
+// C ABI entry points of libowt: descriptor checks, launch planning, tuning, launches.
+#include <array>
+#include <map>
+#include <mutex>
+#include <vector>
+
 #include "owt_host.hpp"
 
 namespace owt {
@@ -17,57 +22,13 @@ void clear_error() { g_err[0] = 0; }
 
 const TileInfo kTiles[NUM_TILES] = {
     {TILE_128x128, 2, 2, 32, 1.00f},
-    {TILE_128x64, 2, 1, 16, 0.85f},
-    {TILE_64x128, 1, 2, 16, 0.85f},
-    {TILE_64x64, 1, 1, 16, 0.70f},
+    {TILE_128x64, 2, 1, 16, 0.90f},
+    {TILE_64x128, 1, 2, 16, 0.90f},
+    {TILE_64x64, 1, 1, 16, 0.75f},
 };
 
 static inline long cdiv(long a, long b) { return (a + b - 1) / b; }
-
-// Cost model in arbitrary time units: every CU works through ceil(WGs/256)
-// work-groups of BM*BN*Kd/splits MACs each at the tile's relative efficiency; a
-// split adds one write and one read of the partial results plus a launch.
-Plan plan_gemm(long M, long Ncols, long Kd, bool vec_ok, bool want_dbias)
-{
-    static const int kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256};
-    int force_tile = -1, force_split = -1;
-    if (const char *e = getenv("OWT_TILE")) force_tile = atoi(e);
-    if (const char *e = getenv("OWT_SPLITK")) force_split = atoi(e);
-    Plan best; memset(&best, 0, sizeof(best));
-    double best_cost = 1e300;
-    for (int t = 0; t < NUM_TILES; t++) {
-        if (!vec_ok && t != TILE_64x64) continue;
-        if (vec_ok && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
-        const TileInfo &ti = kTiles[t];
-        const long BM = 64 * ti.WM, BN = 64 * ti.WN;
-        const long tm = cdiv(M, BM), tn = cdiv(Ncols, BN), ksteps = cdiv(Kd, ti.BK);
-        for (int s0 : kSplits) {
-            long s = s0;
-            if (force_split > 0) {           // tuning/test override: take it as given, capped by the steps there are
-                if (s0 != 1) break;
-                s = force_split < ksteps ? force_split : ksteps;
-            } else if (s > 1 && ksteps / s < 4) {
-                break;
-            }
-            const long per = cdiv(ksteps, s);
-            const long splits = cdiv(ksteps, per);        // drop empty trailing splits
-            const long wgs = tm * tn * splits;
-            const double macs_per_wg = (double)BM * BN * ti.BK * per;
-            double cost = (double)cdiv(wgs, 256) * macs_per_wg / (128.0 * ti.eff);   // ~clocks
-            if (splits > 1) cost += 12000.0 + (double)(splits + 1) * M * Ncols * 4.0 / 1200.0;
-            if (cost < best_cost) {
-                best_cost = cost;
-                best.tile = t; best.splits = (int)splits; best.ksteps = (int)ksteps;
-                best.ksteps_per_split = (int)per; best.tiles_m = (int)tm; best.tiles_n = (int)tn;
-            }
-        }
-    }
-    if (best.splits > 1) {
-        best.partial_bytes = (((size_t)best.splits * M * Ncols * 4) + 255) & ~(size_t)255;
-        best.dbias_partial_bytes = want_dbias ? ((((size_t)best.splits * M * 4) + 255) & ~(size_t)255) : 0;
-    }
-    return best;
-}
+static inline size_t pad256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw)
 {
@@ -81,21 +42,216 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
     return true;
 }
 
-owt_status run_pass(int pass, owt_dtype dt, int va, int vb, GemmParams &p, const Plan &pl,
-                    void *ws, hipStream_t s)
+// ------------------------------------------------------------ launch planning
+// A pass can run as the gather kernel (igemm.hpp; any shape) or, for stride-1
+// forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
+// (kernel, tile, split) that fits is a candidate; a cost model picks one unless
+// owt_conv_autotune has timed them for this descriptor.
+enum { KIND_GATHER = 0, KIND_DIRECT = 1 };
+
+struct PassDims { long M, Ncols, Kd; bool va, vb; };
+
+static PassDims conv_dims(const Geom &g, int pass)
 {
-    static const LaunchFn table[3][2] = {
-        {owt_launch_fwd_f32, owt_launch_fwd_bf16},
-        {owt_launch_data_f32, owt_launch_data_bf16},
-        {owt_launch_filter_f32, owt_launch_filter_bf16},
+    PassDims r;
+    const bool c4 = g.C % 4 == 0, k4 = g.K % 4 == 0;
+    if (pass == OWT_PASS_FWD) {
+        r.M = (long)g.N * g.P * g.Q; r.Ncols = g.K; r.Kd = (long)g.R * g.S * g.C; r.va = r.vb = c4;
+    } else if (pass == OWT_PASS_BWD_DATA) {
+        r.M = (long)g.N * g.H * g.W; r.Ncols = g.C; r.Kd = (long)g.R * g.S * g.K; r.va = k4; r.vb = c4;
+    } else {
+        r.M = g.K; r.Ncols = (long)g.R * g.S * g.C; r.Kd = (long)g.N * g.P * g.Q; r.va = k4; r.vb = c4;
+    }
+    return r;
+}
+
+static void dconv_frame(const Geom &g, int pass, GemmParams &p)
+{
+    if (pass == OWT_PASS_FWD) {
+        p.Hi = g.H; p.Wi = g.W; p.Ho = g.P; p.Wo = g.Q; p.pah = g.ph; p.paw = g.pw; p.Cred = g.C;
+    } else {
+        p.Hi = g.P; p.Wi = g.Q; p.Ho = g.H; p.Wo = g.W; p.pah = g.R - 1 - g.ph; p.paw = g.S - 1 - g.pw; p.Cred = g.K;
+    }
+    p.dWo.set(p.Wo); p.dHoWo.set(p.Ho * p.Wo);
+}
+
+// LDS panel rows the direct kernel needs for 128-row tiles, or -1 when the pass does not qualify.
+static long direct_panel_rows(const Geom &g, int pass, const PassDims &dm)
+{
+    if (pass == OWT_PASS_BWD_FILTER || g.sh != 1 || g.sw != 1 || g.R * g.S == 1) return -1;
+    GemmParams f; memset(&f, 0, sizeof(f));
+    dconv_frame(g, pass, f);
+    if (f.Ho > f.Hi || f.Wo > f.Wi || f.Cred % 4 || (pass == OWT_PASS_BWD_DATA && dm.Ncols % 4)) return -1;
+    auto pin = [&](long m) {
+        const long n = m / (f.Ho * f.Wo), rem = m % (f.Ho * f.Wo);
+        return n * f.Hi * f.Wi + (rem / f.Wo - f.pah) * f.Wi + (rem % f.Wo - f.paw);
     };
-    p.splits = pl.splits; p.ksteps = pl.ksteps; p.ksteps_per_split = pl.ksteps_per_split;
-    p.tiles_m = pl.tiles_m; p.tiles_n = pl.tiles_n;
-    p.partial = pl.splits > 1 ? (float *)ws : nullptr;
-    p.dbias_partial = (pl.splits > 1 && pl.dbias_partial_bytes) ? (float *)((char *)ws + pl.partial_bytes) : nullptr;
-    const hipError_t e = table[pass][dt == OWT_BF16 ? 1 : 0](pl.tile, va, vb, p, s);
+    long need = 0;
+    for (long m0 = 0; m0 < dm.M; m0 += 128) {
+        const long last = (m0 + 128 < dm.M ? m0 + 128 : dm.M) - 1;
+        const long rows = pin(last) - pin(m0) + (g.R - 1) * f.Wi + g.S;
+        if (rows > need) need = rows;
+    }
+    return need;
+}
+
+struct Launch {
+    int kind, tile, splits, steps, steps_per_split, tiles_m, tiles_n, pr;
+    size_t partial_bytes, dbias_bytes;
+    double cost;   // model estimate, ~clocks
+    size_t ws_bytes() const { return partial_bytes + dbias_bytes; }
+};
+
+// Model: the launch's MACs spread over 256 CUs at the tile's relative efficiency, derated when fewer
+// than two wavefronts per SIMD are resident (nothing hides load latency then) and by the unevenness
+// of the last round of work-groups; a split adds a write+read of the partials and a launch.
+static double model_cost(long wgs, int waves_per_wg, int occ, double macs_per_wg, double eff, long splits,
+                         long M, long Ncols)
+{
+    const double per_cu = (double)wgs / 256.0;
+    const double resident = (per_cu < occ ? per_cu : occ) * waves_per_wg / 4.0;
+    const double lat = resident >= 2.0 ? 1.0 : (resident >= 1.0 ? 0.62 + 0.38 * (resident - 1.0) : 0.62 * resident);
+    const double rounds = (double)wgs / (256.0 * occ);
+    const double tail = rounds > 1.0 ? 0.5 + 0.5 * rounds / (double)cdiv(wgs, 256L * occ) : 1.0;
+    double cost = (double)wgs * macs_per_wg / 256.0 / (128.0 * eff * lat * tail);
+    if (splits > 1) cost += 14000.0 + (double)(splits + 1) * M * Ncols * 4.0 / 1300.0;
+    return cost;
+}
+
+static const size_t kMaxPartialBytes = (size_t)192 << 20;
+
+static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db, std::vector<Launch> &out)
+{
+    int force_tile = -1, force_split = -1;
+    if (const char *e = getenv("OWT_TILE")) force_tile = atoi(e);
+    if (const char *e = getenv("OWT_SPLITK")) force_split = atoi(e);
+    const bool no_direct = getenv("OWT_NO_DIRECT") != nullptr;
+    const bool vec = dm.va && dm.vb;
+
+    auto add = [&](int kind, int tile, int pr, long steps, long s, double macs_per_step_wg, int occ, double eff) {
+        if (force_split > 0) s = force_split < steps ? force_split : steps;
+        const long per = cdiv(steps, s), splits = cdiv(steps, per);     // drops empty trailing splits
+        const TileInfo &ti = kTiles[tile];
+        const long tm = cdiv(dm.M, 64 * ti.WM), tn = cdiv(dm.Ncols, 64 * ti.WN);
+        Launch l; memset(&l, 0, sizeof(l));
+        l.kind = kind; l.tile = tile; l.pr = pr; l.splits = (int)splits; l.steps = (int)steps;
+        l.steps_per_split = (int)per; l.tiles_m = (int)tm; l.tiles_n = (int)tn;
+        if (splits > 1) {
+            l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+            l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+            if (l.partial_bytes > kMaxPartialBytes && force_split <= 0) return;
+        }
+        l.cost = model_cost(tm * tn * splits, ti.WM * ti.WN, occ, macs_per_step_wg * per, eff, splits, dm.M, dm.Ncols);
+        for (const Launch &o : out)
+            if (o.kind == l.kind && o.tile == l.tile && o.splits == l.splits) return;
+        out.push_back(l);
+    };
+
+    static const long kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256};
+    const long rows = no_direct ? -1 : direct_panel_rows(g, pass, dm);
+    if (rows >= 0 && rows <= 256) {
+        const int pr = rows <= 160 ? 160 : 256;
+        const long cred = pass == OWT_PASS_FWD ? g.C : g.K;
+        for (int t : {TILE_128x128, TILE_128x64}) {
+            if (force_tile >= 0 && force_tile != t) continue;
+            const long bk = t == TILE_128x128 ? 32 : 16, chunks = cdiv(cred, bk);
+            const double macs = 128.0 * 64 * kTiles[t].WN * bk * g.R * g.S;
+            for (long s : kSplits) {
+                if (s > 1 && (chunks / s < 2 || s > 8)) break;
+                add(KIND_DIRECT, t, pr, chunks, s, macs, t == TILE_128x128 ? 2 : 5, t == TILE_128x128 ? 1.25 : 1.1);
+                if (force_split > 0) break;
+            }
+        }
+    }
+    const bool have_direct = !out.empty();      // the gather kernel is only the fallback
+    for (int t = 0; t < NUM_TILES && !have_direct; t++) {
+        if (!vec && t != TILE_64x64) continue;
+        if (vec && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
+        const TileInfo &ti = kTiles[t];
+        const long ksteps = cdiv(dm.Kd, ti.BK);
+        const long tiles = cdiv(dm.M, 64 * ti.WM) * cdiv(dm.Ncols, 64 * ti.WN);
+        const double macs = 64.0 * ti.WM * 64 * ti.WN * ti.BK;
+        for (long s : kSplits) {
+            if (s > 1 && (ksteps / s < 4 || tiles * s > 4096)) break;
+            add(KIND_GATHER, t, 0, ksteps, s, macs, t == TILE_128x128 ? 2 : 5, ti.eff);
+            if (force_split > 0) break;
+        }
+    }
+}
+
+typedef std::array<int, 15> PlanKey;
+static std::map<PlanKey, Launch> g_tuned;
+static std::mutex g_tuned_mutex;
+
+static PlanKey plan_key(const Geom &g, int pass, owt_dtype dt)
+{
+    return PlanKey{g.N, g.C, g.H, g.W, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, pass, (int)dt, 0, 0};
+}
+
+static bool env_overrides() { return getenv("OWT_TILE") || getenv("OWT_SPLITK") || getenv("OWT_NO_DIRECT"); }
+
+static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, bool want_db, bool use_cache)
+{
+    if (use_cache && !env_overrides()) {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        auto it = g_tuned.find(plan_key(g, pass, dt));
+        if (it != g_tuned.end()) return it->second;
+    }
+    std::vector<Launch> c;
+    enumerate(g, pass, dm, want_db, c);
+    size_t best = 0;
+    for (size_t i = 1; i < c.size(); i++)
+        if (c[i].cost < c[best].cost) best = i;
+    return c[best];
+}
+
+// Workspace every candidate fits in (so a tuned choice never outgrows the caller's buffer).
+static size_t max_workspace(const Geom &g, int pass, const PassDims &dm, bool want_db)
+{
+    std::vector<Launch> c;
+    enumerate(g, pass, dm, want_db, c);
+    size_t m = 0;
+    for (const Launch &l : c) m = l.ws_bytes() > m ? l.ws_bytes() : m;
+    return m;
+}
+
+static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, GemmParams p, const Launch &l,
+                         void *ws, hipStream_t s)
+{
+    p.g = g; p.M = (int)dm.M; p.Ncols = (int)dm.Ncols; p.Kd = (int)dm.Kd;
+    p.splits = l.splits; p.ksteps = l.steps; p.ksteps_per_split = l.steps_per_split;
+    p.tiles_m = l.tiles_m; p.tiles_n = l.tiles_n;
+    p.partial = l.splits > 1 ? (float *)ws : nullptr;
+    p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.partial_bytes) : nullptr;
+    const bool bf = dt == OWT_BF16;
+    hipError_t e;
+    if (l.kind == KIND_DIRECT) {
+        dconv_frame(g, pass, p);
+        if (pass == OWT_PASS_FWD) e = bf ? owt_launch_dconv_fwd_bf16(l.tile, l.pr, p, s) : owt_launch_dconv_fwd_f32(l.tile, l.pr, p, s);
+        else e = bf ? owt_launch_dconv_data_bf16(l.tile, l.pr, p, s) : owt_launch_dconv_data_f32(l.tile, l.pr, p, s);
+    } else {
+        static const LaunchFn table[3][2] = {
+            {owt_launch_fwd_f32, owt_launch_fwd_bf16},
+            {owt_launch_data_f32, owt_launch_data_bf16},
+            {owt_launch_filter_f32, owt_launch_filter_bf16},
+        };
+        e = table[pass][bf ? 1 : 0](l.tile, dm.va ? 4 : 1, dm.vb ? 4 : 1, p, s);
+    }
     if (e != hipSuccess) return fail(OWT_ELAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
     return OWT_OK;
+}
+
+static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims &dm, const Launch &l)
+{
+    static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
+    const TileInfo &ti = kTiles[l.tile];
+    if (l.kind == KIND_DIRECT)
+        return snprintf(buf, n, "dconv %s %s tile128x%dx%d panel%d splitk%d grid%dx%d", pn[pass],
+                        dt == OWT_BF16 ? "bf16" : "f32", 64 * ti.WN, l.tile == TILE_128x128 ? 32 : 16, l.pr, l.splits,
+                        l.tiles_m * l.tiles_n, l.splits);
+    return snprintf(buf, n, "igemm %s %s tile%dx%dx%d vec%d/%d splitk%d grid%dx%d", pn[pass],
+                    dt == OWT_BF16 ? "bf16" : "f32", 64 * ti.WM, 64 * ti.WN, ti.BK, dm.va ? 4 : 1, dm.vb ? 4 : 1,
+                    l.splits, l.tiles_m * l.tiles_n, l.splits);
 }
 
 // ----------------------------------------------------------------- checking
@@ -120,22 +276,6 @@ static owt_status check_conv(const owt_conv_desc *d, Geom &g)
     return OWT_OK;
 }
 
-struct PassDims { long M, Ncols, Kd; bool va, vb; };
-
-static PassDims conv_dims(const Geom &g, int pass)
-{
-    PassDims r;
-    const bool c4 = g.C % 4 == 0, k4 = g.K % 4 == 0;
-    if (pass == OWT_PASS_FWD) {
-        r.M = (long)g.N * g.P * g.Q; r.Ncols = g.K; r.Kd = (long)g.R * g.S * g.C; r.va = r.vb = c4;
-    } else if (pass == OWT_PASS_BWD_DATA) {
-        r.M = (long)g.N * g.H * g.W; r.Ncols = g.C; r.Kd = (long)g.R * g.S * g.K; r.va = k4; r.vb = c4;
-    } else {
-        r.M = g.K; r.Ncols = (long)g.R * g.S * g.C; r.Kd = (long)g.N * g.P * g.Q; r.va = k4; r.vb = c4;
-    }
-    return r;
-}
-
 static owt_status check_ptr(const void *p, const char *name)
 {
     if (!p) return fail(OWT_EINVAL, "%s is NULL", name);
@@ -145,18 +285,43 @@ static owt_status check_ptr(const void *p, const char *name)
 
 #define OWT_TRY(expr) do { owt_status st_ = (expr); if (st_ != OWT_OK) return st_; } while (0)
 
-static owt_status conv_pass(const Geom &g, int pass, owt_dtype dt, GemmParams &p, bool want_db,
-                            void *ws, size_t ws_bytes, hipStream_t s)
+static owt_status check_ws(const Launch &l, void *ws, size_t ws_bytes)
+{
+    if (l.ws_bytes() > ws_bytes)
+        return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", l.ws_bytes(), ws_bytes);
+    if (l.ws_bytes() && (!ws || !aligned16(ws))) return fail(OWT_EINVAL, "ws is NULL or misaligned");
+    return OWT_OK;
+}
+
+static owt_status conv_pass(const Geom &g, int pass, owt_dtype dt, const GemmParams &p, bool want_db,
+                            void *ws, size_t ws_bytes, hipStream_t s, bool use_cache)
 {
     const PassDims dm = conv_dims(g, pass);
-    const Plan pl = plan_gemm(dm.M, dm.Ncols, dm.Kd, dm.va && dm.vb, want_db);
-    if (pl.total_bytes() > ws_bytes)
-        return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", pl.total_bytes(), ws_bytes);
-    if (pl.total_bytes() && (!ws || !aligned16(ws))) return fail(OWT_EINVAL, "ws is NULL or misaligned");
-    if ((long)pl.splits * dm.M * dm.Ncols > kMaxElems * 4L)
-        return fail(OWT_EUNSUPPORTED, "split-K partials too large");
-    p.g = g; p.M = (int)dm.M; p.Ncols = (int)dm.Ncols; p.Kd = (int)dm.Kd;
-    return run_pass(pass, dt, dm.va ? 4 : 1, dm.vb ? 4 : 1, p, pl, ws, s);
+    const Launch l = choose(g, pass, dt, dm, want_db, use_cache);
+    OWT_TRY(check_ws(l, ws, ws_bytes));
+    return launch(g, pass, dt, dm, p, l, ws, s);
+}
+
+static GemmParams fwd_params(const owt_conv_desc *d, const void *x, const void *w, const float *bias, void *y)
+{
+    GemmParams p; memset(&p, 0, sizeof(p));
+    p.a = x; p.b = w; p.out = y; p.bias = bias; p.flags = d->flags;
+    return p;
+}
+static GemmParams data_params(const owt_conv_desc *d, const void *dy, const void *y, const void *w, void *dx)
+{
+    GemmParams p; memset(&p, 0, sizeof(p));
+    p.a = dy; p.b = w; p.out = dx; p.flags = d->flags;
+    p.mask = (d->flags & OWT_RELU) ? y : nullptr;
+    return p;
+}
+static GemmParams filter_params(const owt_conv_desc *d, const void *x, const void *dy, const void *y, float alpha,
+                                float beta, float *dw, float *db)
+{
+    GemmParams p; memset(&p, 0, sizeof(p));
+    p.a = dy; p.b = x; p.out = dw; p.flags = d->flags; p.alpha = alpha; p.beta = beta; p.dbias = db;
+    p.mask = (d->flags & OWT_RELU) ? y : nullptr;
+    return p;
 }
 
 }  // namespace owt
@@ -184,16 +349,27 @@ int owt_selftest_host(void)
                 if (f.div(n) != n / d) { fail(OWT_EINVAL, "FastDiv wrong: %u / %u", n, d); return 1; }
         }
     }
-    // the planner never asks for more splits than there are BK steps and covers all of them
-    for (long M : {1L, 64L, 125L, 21632L, 387200L})
-        for (long Nc : {1L, 64L, 363L, 3456L})
-            for (long Kd : {1L, 27L, 363L, 9216L, 387200L}) {
-                const Plan pl = plan_gemm(M, Nc, Kd, true, true);
-                if (pl.splits < 1 || (long)pl.splits * pl.ksteps_per_split < pl.ksteps ||
-                    (long)(pl.splits - 1) * pl.ksteps_per_split >= pl.ksteps) {
-                    fail(OWT_EINVAL, "bad plan for %ld x %ld x %ld", M, Nc, Kd); return 2;
+    // every candidate launch covers all reduction steps with no empty split, and fits its workspace bound
+    static const int shapes[][7] = {{128, 3, 224, 64, 11, 4, 2}, {128, 64, 27, 192, 5, 1, 2}, {128, 192, 13, 384, 3, 1, 1},
+                                    {128, 384, 13, 256, 3, 1, 1}, {8, 3, 32, 16, 5, 1, 2}, {2, 8, 7, 4, 7, 1, 0},
+                                    {1024, 256, 13, 256, 3, 1, 1}, {128, 9216, 1, 512, 1, 1, 0}, {1, 1, 3, 1, 3, 1, 1}};
+    for (const auto &sh : shapes) {
+        Geom g;
+        if (!fill_geom(g, sh[0], sh[1], sh[2], sh[2], sh[3], sh[4], sh[4], sh[5], sh[5], sh[6], sh[6])) return 2;
+        for (int pass = 0; pass < 3; pass++) {
+            const PassDims dm = conv_dims(g, pass);
+            std::vector<Launch> c;
+            enumerate(g, pass, dm, pass == OWT_PASS_BWD_FILTER, c);
+            if (c.empty()) { fail(OWT_EINVAL, "no candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 3; }
+            const size_t bound = max_workspace(g, pass, dm, pass == OWT_PASS_BWD_FILTER);
+            for (const Launch &l : c)
+                if (l.splits < 1 || (long)l.splits * l.steps_per_split < l.steps ||
+                    (long)(l.splits - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
+                    (l.kind == KIND_DIRECT && (l.pr > 256 || direct_panel_rows(g, pass, dm) > l.pr))) {
+                    fail(OWT_EINVAL, "bad candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 4;
                 }
-            }
+        }
+    }
     return 0;
 }
 
@@ -202,8 +378,7 @@ size_t owt_conv_workspace_bytes(const owt_conv_desc *d, int pass)
     Geom g;
     if (pass < 0 || pass > 2) { fail(OWT_EINVAL, "pass must be 0, 1 or 2"); return (size_t)-1; }
     if (check_conv(d, g) != OWT_OK) return (size_t)-1;
-    const PassDims dm = conv_dims(g, pass);
-    return plan_gemm(dm.M, dm.Ncols, dm.Kd, dm.va && dm.vb, pass == OWT_PASS_BWD_FILTER).total_bytes();
+    return max_workspace(g, pass, conv_dims(g, pass), pass == OWT_PASS_BWD_FILTER);
 }
 
 int owt_conv_plan_describe(const owt_conv_desc *d, int pass, char *buf, size_t buf_bytes)
@@ -212,12 +387,7 @@ int owt_conv_plan_describe(const owt_conv_desc *d, int pass, char *buf, size_t b
     if (pass < 0 || pass > 2 || !buf || buf_bytes == 0) { fail(OWT_EINVAL, "bad pass or buffer"); return -1; }
     if (check_conv(d, g) != OWT_OK) return -1;
     const PassDims dm = conv_dims(g, pass);
-    const Plan pl = plan_gemm(dm.M, dm.Ncols, dm.Kd, dm.va && dm.vb, pass == OWT_PASS_BWD_FILTER);
-    static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
-    const TileInfo &ti = kTiles[pl.tile];
-    return snprintf(buf, buf_bytes, "igemm %s %s tile%dx%dx%d vec%d/%d splitk%d grid%dx%d", pn[pass],
-                    d->dtype == OWT_BF16 ? "bf16" : "f32", 64 * ti.WM, 64 * ti.WN, ti.BK, dm.va ? 4 : 1,
-                    dm.vb ? 4 : 1, pl.splits, pl.tiles_m * pl.tiles_n, pl.splits);
+    return describe(buf, buf_bytes, pass, d->dtype, dm, choose(g, pass, d->dtype, dm, pass == OWT_PASS_BWD_FILTER, true));
 }
 
 owt_status owt_conv_fwd(const owt_conv_desc *d, const void *x, const void *w, const float *bias,
@@ -227,9 +397,8 @@ owt_status owt_conv_fwd(const owt_conv_desc *d, const void *x, const void *w, co
     OWT_TRY(check_conv(d, g));
     OWT_TRY(check_ptr(x, "x")); OWT_TRY(check_ptr(w, "w")); OWT_TRY(check_ptr(y, "y"));
     if (d->flags & OWT_BIAS) OWT_TRY(check_ptr(bias, "bias"));
-    GemmParams p; memset(&p, 0, sizeof(p));
-    p.a = x; p.b = w; p.out = y; p.bias = bias; p.flags = d->flags;
-    return conv_pass(g, OWT_PASS_FWD, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream);
+    return conv_pass(g, OWT_PASS_FWD, d->dtype, fwd_params(d, x, w, bias, y), false, ws, ws_bytes,
+                     (hipStream_t)hip_stream, true);
 }
 
 owt_status owt_conv_bwd_data(const owt_conv_desc *d, const void *dy, const void *y_or_null,
@@ -239,10 +408,8 @@ owt_status owt_conv_bwd_data(const owt_conv_desc *d, const void *dy, const void 
     OWT_TRY(check_conv(d, g));
     OWT_TRY(check_ptr(dy, "dy")); OWT_TRY(check_ptr(w, "w")); OWT_TRY(check_ptr(dx, "dx"));
     if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
-    GemmParams p; memset(&p, 0, sizeof(p));
-    p.a = dy; p.b = w; p.out = dx; p.flags = d->flags;
-    p.mask = (d->flags & OWT_RELU) ? y_or_null : nullptr;
-    return conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream);
+    return conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, data_params(d, dy, y_or_null, w, dx), false, ws, ws_bytes,
+                     (hipStream_t)hip_stream, true);
 }
 
 owt_status owt_conv_bwd_filter(const owt_conv_desc *d, const void *x, const void *dy,
@@ -254,11 +421,55 @@ owt_status owt_conv_bwd_filter(const owt_conv_desc *d, const void *x, const void
     OWT_TRY(check_ptr(x, "x")); OWT_TRY(check_ptr(dy, "dy")); OWT_TRY(check_ptr(dw, "dw"));
     if (dbias_or_null) OWT_TRY(check_ptr(dbias_or_null, "dbias"));
     if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
-    GemmParams p; memset(&p, 0, sizeof(p));
-    p.a = dy; p.b = x; p.out = dw; p.flags = d->flags; p.alpha = alpha; p.beta = beta;
-    p.dbias = dbias_or_null;
-    p.mask = (d->flags & OWT_RELU) ? y_or_null : nullptr;
-    return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, p, true, ws, ws_bytes, (hipStream_t)hip_stream);
+    return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, filter_params(d, x, dy, y_or_null, alpha, beta, dw, dbias_or_null),
+                     true, ws, ws_bytes, (hipStream_t)hip_stream, true);
+}
+
+owt_status owt_conv_autotune(const owt_conv_desc *d, int pass, const void *x, const void *w, const float *bias,
+                             void *y, const void *dy, void *dx, float *dw, float *dbias_or_null, void *ws,
+                             size_t ws_bytes, void *hip_stream)
+{
+    Geom g;
+    if (pass < 0 || pass > 2) return fail(OWT_EINVAL, "pass must be 0, 1 or 2");
+    OWT_TRY(check_conv(d, g));
+    OWT_TRY(check_ptr(w, "w"));
+    GemmParams p;
+    if (pass == OWT_PASS_FWD) {
+        OWT_TRY(check_ptr(x, "x")); OWT_TRY(check_ptr(y, "y"));
+        if (d->flags & OWT_BIAS) OWT_TRY(check_ptr(bias, "bias"));
+        p = fwd_params(d, x, w, bias, y);
+    } else {
+        OWT_TRY(check_ptr(dy, "dy"));
+        if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y, "y (needed for the ReLU mask)"));
+        if (pass == OWT_PASS_BWD_DATA) { OWT_TRY(check_ptr(dx, "dx")); p = data_params(d, dy, y, w, dx); }
+        else { OWT_TRY(check_ptr(x, "x")); OWT_TRY(check_ptr(dw, "dw")); p = filter_params(d, x, dy, y, 1.f, 0.f, dw, dbias_or_null); }
+    }
+    const PassDims dm = conv_dims(g, pass);
+    std::vector<Launch> c;
+    enumerate(g, pass, dm, pass == OWT_PASS_BWD_FILTER, c);
+    for (const Launch &l : c) OWT_TRY(check_ws(l, ws, ws_bytes));
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
+        return fail(OWT_ELAUNCH, "hipEventCreate failed");
+    int best = -1; float best_ms = 0.f;
+    owt_status st = OWT_OK;
+    for (size_t i = 0; i < c.size() && st == OWT_OK; i++) {
+        st = launch(g, pass, d->dtype, dm, p, c[i], ws, s);                       // warm-up
+        if (st != OWT_OK) break;
+        hipEventRecord(e0, s);
+        for (int r = 0; r < 3 && st == OWT_OK; r++) st = launch(g, pass, d->dtype, dm, p, c[i], ws, s);
+        hipEventRecord(e1, s);
+        if (hipEventSynchronize(e1) != hipSuccess) { st = fail(OWT_ELAUNCH, "hipEventSynchronize failed"); break; }
+        float ms = 0.f;
+        hipEventElapsedTime(&ms, e0, e1);
+        if (best < 0 || ms < best_ms) { best = (int)i; best_ms = ms; }
+    }
+    hipEventDestroy(e0); hipEventDestroy(e1);
+    if (st != OWT_OK) return st;
+    std::lock_guard<std::mutex> lk(g_tuned_mutex);
+    g_tuned[plan_key(g, pass, d->dtype)] = c[best];
+    return OWT_OK;
 }
 
 // ------------------------------------------------------- fully-connected shard
@@ -283,14 +494,10 @@ size_t owt_fc_workspace_bytes(const owt_fc_desc *d, int pass)
     Geom g; int ol;
     if (pass < 0 || pass > 2) { fail(OWT_EINVAL, "pass must be 0, 1 or 2"); return (size_t)-1; }
     if (check_fc(d, g, ol) != OWT_OK) return (size_t)-1;
-    if (pass == OWT_PASS_FWD) {
-        const PassDims dm = conv_dims(g, OWT_PASS_FWD);
-        return plan_gemm(dm.M, dm.Ncols, dm.Kd, dm.va && dm.vb, false).total_bytes();
-    }
+    if (pass == OWT_PASS_FWD) return max_workspace(g, OWT_PASS_FWD, conv_dims(g, OWT_PASS_FWD), false);
     // the backward call runs the data pass, then the filter pass, on one scratch area
-    const PassDims d1 = conv_dims(g, OWT_PASS_BWD_DATA), d2 = conv_dims(g, OWT_PASS_BWD_FILTER);
-    const size_t a = plan_gemm(d1.M, d1.Ncols, d1.Kd, d1.va && d1.vb, false).total_bytes();
-    const size_t b = plan_gemm(d2.M, d2.Ncols, d2.Kd, d2.va && d2.vb, true).total_bytes();
+    const size_t a = max_workspace(g, OWT_PASS_BWD_DATA, conv_dims(g, OWT_PASS_BWD_DATA), false);
+    const size_t b = max_workspace(g, OWT_PASS_BWD_FILTER, conv_dims(g, OWT_PASS_BWD_FILTER), true);
     return a > b ? a : b;
 }
 
@@ -303,7 +510,7 @@ owt_status owt_fc_shard_fwd(const owt_fc_desc *d, const void *x, const void *w, 
     if (d->flags & OWT_BIAS) OWT_TRY(check_ptr(bias, "bias"));
     GemmParams p; memset(&p, 0, sizeof(p));
     p.a = x; p.b = w; p.out = y; p.bias = bias; p.flags = d->flags;
-    return conv_pass(g, OWT_PASS_FWD, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream);
+    return conv_pass(g, OWT_PASS_FWD, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, false);
 }
 
 owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, const void *y_or_null,
@@ -318,19 +525,19 @@ owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, 
     if (dx_partial_or_null) OWT_TRY(check_ptr(dx_partial_or_null, "dx_partial"));
     if (dbias_or_null) OWT_TRY(check_ptr(dbias_or_null, "dbias"));
     if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
-    if (ws_bytes < owt_fc_workspace_bytes(d, OWT_PASS_BWD_DATA))
-        return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu",
-                    owt_fc_workspace_bytes(d, OWT_PASS_BWD_DATA), ws_bytes);
+    const size_t need = owt_fc_workspace_bytes(d, OWT_PASS_BWD_DATA);
+    if (ws_bytes < need) return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
+    if (need && (!ws || !aligned16(ws))) return fail(OWT_EINVAL, "ws is NULL or misaligned");
     const void *mask = (d->flags & OWT_RELU) ? y_or_null : nullptr;
     if (dx_partial_or_null) {
         GemmParams p; memset(&p, 0, sizeof(p));
         p.a = dy; p.b = w; p.out = dx_partial_or_null; p.flags = d->flags; p.mask = mask;
-        OWT_TRY(conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream));
+        OWT_TRY(conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, false));
     }
     GemmParams p; memset(&p, 0, sizeof(p));
     p.a = dy; p.b = x; p.out = dw; p.flags = d->flags; p.alpha = alpha; p.beta = beta;
     p.dbias = dbias_or_null; p.mask = mask;
-    return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, p, true, ws, ws_bytes, (hipStream_t)hip_stream);
+    return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, p, true, ws, ws_bytes, (hipStream_t)hip_stream, false);
 }
 
 }  // extern "C"

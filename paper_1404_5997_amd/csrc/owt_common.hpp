@@ -45,6 +45,11 @@ struct GemmParams {
     int splits, ksteps, ksteps_per_split;
     int tiles_m, tiles_n;
     unsigned flags;
+    // Direct (panel-resident) stride-1 kernel only: the gathered tensor is Hi x Wi x Cred per
+    // image, the result Ho x Wo x Ncols; output pixel (ho,wo) reads input pixels
+    // (ho-pah+r, wo-paw+s), r < R, s < S.
+    int Hi, Wi, Ho, Wo, pah, paw, Cred;
+    FastDiv dWo, dHoWo;
 };
 
 struct bf16_t { uint16_t bits; };

@@ -20,16 +20,6 @@ struct TileInfo { int id, WM, WN, BK; float eff; };
 enum { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x128 = 2, TILE_64x64 = 3, NUM_TILES = 4 };
 extern const TileInfo kTiles[NUM_TILES];
 
-struct Plan {
-    int tile, splits, ksteps, ksteps_per_split, tiles_m, tiles_n;
-    size_t partial_bytes, dbias_partial_bytes;   // workspace, in this order
-    size_t total_bytes() const { return partial_bytes + dbias_partial_bytes; }
-};
-
-// Chooses tile shape and split-K factor for a GEMM view of M x Ncols x Kd.
-// vec_ok == false restricts the choice to the scalar-gather instantiation.
-Plan plan_gemm(long M, long Ncols, long Kd, bool vec_ok, bool want_dbias);
-
 bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw);
 
 // One entry per (pass, storage type); defined in igemm_inst.hip, built once per pair.
@@ -41,8 +31,10 @@ hipError_t owt_launch_data_bf16(int, int, int, const GemmParams &, hipStream_t);
 hipError_t owt_launch_filter_f32(int, int, int, const GemmParams &, hipStream_t);
 hipError_t owt_launch_filter_bf16(int, int, int, const GemmParams &, hipStream_t);
 
-// Runs one planned GEMM pass (main kernel + split-K reduction when needed).
-owt_status run_pass(int pass, owt_dtype dt, int va, int vb, GemmParams &p, const Plan &pl,
-                    void *ws, hipStream_t s);
+// Panel-resident stride-1 kernel (dconv_inst.hip), forward and backward-data.
+hipError_t owt_launch_dconv_fwd_f32(int tile, int pr, const GemmParams &, hipStream_t);
+hipError_t owt_launch_dconv_fwd_bf16(int tile, int pr, const GemmParams &, hipStream_t);
+hipError_t owt_launch_dconv_data_f32(int tile, int pr, const GemmParams &, hipStream_t);
+hipError_t owt_launch_dconv_data_bf16(int tile, int pr, const GemmParams &, hipStream_t);
 
 }  // namespace owt

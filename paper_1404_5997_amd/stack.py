@@ -13,7 +13,7 @@ build.
 import torch
 
 from . import (OWT_BF16, OWT_BIAS, OWT_F32, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER, OWT_PASS_FWD, OWT_RELU,
-               conv_desc, fc_desc, owt_conv_bwd_data, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
+               conv_desc, fc_desc, owt_conv_autotune, owt_conv_bwd_data, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
                owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_maxpool_bwd, owt_maxpool_fwd)
 
 
@@ -159,6 +159,20 @@ class ConvStack:
     def step(self):
         self.forward()
         self.backward()
+
+    def autotune(self):
+        """Let the library time its kernel variants for every convolution pass of the stack on the
+        stack's own buffers (owt_conv_autotune).  Call after load() and after the top gradient is set."""
+        self.step()     # gives every buffer the contents a real step leaves in it
+        for li, e in enumerate(self.L):
+            prev = self.L[li - 1] if li > 0 else None
+            dx = (prev["da"] if prev["pool"] else prev["dy"]) if prev is not None else None
+            owt_conv_autotune(e["desc"], OWT_PASS_FWD, e["x"], e["w"], e["b"], e["y"], None, None, None, None, self.ws)
+            if dx is not None:
+                owt_conv_autotune(e["desc"], OWT_PASS_BWD_DATA, None, e["w"], None, e["y"], e["dy"], dx, None, None, self.ws)
+            owt_conv_autotune(e["desc"], OWT_PASS_BWD_FILTER, e["x"], e["w"], None, e["y"], e["dy"], None, e["dw"],
+                              e["db"], self.ws)
+        self.step()
 
     # ----------------------------------------------------------- work counters
     def conv_flops(self):

@@ -126,15 +126,50 @@ def test_flags_and_scaling_variants():
     layer_parity(6, 8, 9, 9, 12, 3, 3, 1, 1, alpha=0.5, beta=-0.25, seed=54)
 
 
-@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (2, 1), (3, 1), (0, 3), (1, 4), (2, 2), (3, 8)])
-def test_every_tile_shape_and_split_k(tile, split):
-    # The planner is overridden so each instantiation and the two-pass reduction are exercised.
+@pytest.mark.parametrize("tile,split,direct", [(0, 1, 0), (1, 1, 0), (2, 1, 0), (3, 1, 0), (0, 3, 0), (1, 4, 0),
+                                               (2, 2, 0), (3, 8, 0), (0, 1, 1), (1, 1, 1), (0, 2, 1), (1, 3, 1)])
+def test_every_tile_shape_and_split_k(tile, split, direct):
+    # The planner is overridden so each instantiation of the gather kernel (direct = 0) and of the
+    # panel-resident stride-1 kernel (direct = 1), and the two-pass split reduction, are exercised.
     os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(tile), str(split)
+    if not direct:
+        os.environ["OWT_NO_DIRECT"] = "1"
     try:
-        layer_parity(4, 32, 13, 13, 136, 3, 3, 1, 1, seed=60 + tile)     # M = 676, ragged in every tile
+        layer_parity(4, 40, 13, 13, 136, 3, 3, 1, 1, seed=60 + tile)     # M = 676, ragged in every tile and chunk
         layer_parity(2, 32, 13, 13, 136, 3, 3, 1, 1, dt="bf16", seed=70 + tile)
+        if direct:
+            layer_parity(3, 64, 27, 27, 72, 5, 5, 1, 2, seed=80 + tile)      # 240-row panel
+            layer_parity(2, 8, 9, 14, 12, 3, 5, 1, (1, 2), seed=84 + tile)   # R != S, H != W
+            layer_parity(2, 8, 12, 12, 8, 3, 3, 1, 0, seed=88 + tile)        # pad 0: forward direct, bwd-data gathers
     finally:
-        del os.environ["OWT_TILE"], os.environ["OWT_SPLITK"]
+        for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_DIRECT"):
+            os.environ.pop(k, None)
+
+
+def test_autotune_keeps_results_and_is_remembered():
+    m = owt()
+    geom, x, w, b, dy = si.config2(16)
+    case = ConvCase(16, 192, 13, 13, 384, 3, 3, 1, 1)
+    y0 = case.fwd(x, w, b)
+    dx0 = case.bwd_data(dy, y0, w)
+    dw0, db0 = case.bwd_filter(x, dy, y0)
+    before = [m.owt_conv_plan_describe(case.desc, p) for p in range(3)]
+    xd, wd, bd, dyd, yd = to_dev(x), to_dev(w), to_dev(b), to_dev(dy), to_dev(y0)
+    out_y, out_dx = empty(case.shape_y), empty(case.shape_x)
+    out_dw, out_db = empty(case.shape_w), empty((384,))
+    for p in range(3):
+        m.owt_conv_autotune(case.desc, p, xd, wd, bd, out_y if p == 0 else yd, dyd, out_dx, out_dw, out_db, case.ws(p))
+    after = [m.owt_conv_plan_describe(case.desc, p) for p in range(3)]
+    say("plans before", before)
+    say("plans after ", after)
+    assert after == [m.owt_conv_plan_describe(case.desc, p) for p in range(3)]
+    assert_close(case.fwd(x, w, b), y0, "f32", "fwd after tuning")
+    assert_close(case.bwd_data(dy, y0, w), dx0, "f32", "bwd_data after tuning")
+    dw1, db1 = case.bwd_filter(x, dy, y0)
+    assert_close(dw1, dw0, "f32", "dw after tuning")
+    assert_close(db1, db0, "f32", "db after tuning")
+    ref = oracle.conv_fwd(x, w, b, 1, 1, True)
+    assert_close(to_host(out_y), ref, "f32", "y written by the tuning runs")
 
 
 def test_run_to_run_bit_equality():
