@@ -105,6 +105,16 @@ owt_status owt_conv_fwd(const owt_conv_desc *d, const void *x, const void *w, co
 owt_status owt_conv_bwd_data(const owt_conv_desc *d, const void *dy, const void *y_or_null,
                              const void *w, void *dx, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* owt_conv_bwd_data with the backward pass of the PRECEDING ReLU fused into its
+ * store: x is this layer's input [N,H,W,C]; where x <= 0 the stored dx is 0.
+ * Use it when x is itself the output of a bias+ReLU layer: the result is that
+ * layer's dz, and its own backward calls can then run without OWT_RELU.  Saves
+ * every later kernel a second read of the mask source.  Same arithmetic as
+ * Section 4, backward step 2, only the place where the mask is applied moves. */
+owt_status owt_conv_bwd_data_relu_in(const owt_conv_desc *d, const void *dy, const void *y_or_null,
+                                     const void *w, const void *x, void *dx, void *ws, size_t ws_bytes,
+                                     void *hip_stream);
+
 /* Convolution backward w.r.t. filters and bias (Section 4, backward step 2):
  *   dw[k,r,s,c] = alpha * sum_{n,p,q} dz[n,p,q,k] * x[n, p*stride_h-pad_h+r, q*stride_w-pad_w+s, c] + beta * dw
  *   dbias[k]    = alpha * sum_{n,p,q} dz[n,p,q,k] + beta * dbias          (skipped when dbias_or_null is NULL)
@@ -160,6 +170,15 @@ owt_status owt_maxpool_fwd(int N, int H, int W, int C, int win, int stride, owt_
  * (p,q) whose argmax names (h,w); dx [N,H,W,C] is written everywhere. */
 owt_status owt_maxpool_bwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
                            const void *dy, const unsigned char *argmax, void *dx, void *hip_stream);
+
+/* owt_maxpool_bwd with the backward pass of a ReLU that sits between a
+ * convolution and this pooling fused in: y_pooled [N,P,Q,C] is the pooling
+ * OUTPUT; windows whose pooled value is <= 0 contribute nothing.  Exactly equal
+ * to masking dx with [pool input > 0] afterwards, because the element a window
+ * routes its gradient to holds that window's maximum. */
+owt_status owt_maxpool_bwd_relu(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                                const void *dy, const unsigned char *argmax, const void *y_pooled, void *dx,
+                                void *hip_stream);
 
 /* Message for the calling thread's most recent non-OK return ("" if none).
  * Points at thread-local static storage; valid until the thread's next call. */

@@ -23,6 +23,7 @@ EXPORTS = (
     "owt_conv_workspace_bytes", "owt_fc_workspace_bytes", "owt_conv_fwd", "owt_conv_bwd_data",
     "owt_conv_bwd_filter", "owt_fc_shard_fwd", "owt_fc_shard_bwd", "owt_maxpool_fwd",
     "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe", "owt_conv_autotune",
+    "owt_conv_bwd_data_relu_in", "owt_maxpool_bwd_relu",
 )
 
 
@@ -56,6 +57,8 @@ _lib.owt_fc_workspace_bytes.restype = _sz
 _lib.owt_fc_workspace_bytes.argtypes = [_fd, _i]
 _lib.owt_conv_fwd.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_conv_bwd_data.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.owt_conv_bwd_data_relu_in.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.owt_maxpool_bwd_relu.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]
 _lib.owt_conv_bwd_filter.argtypes = [_cd, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_conv_autotune.argtypes = [_cd, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_fwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -151,6 +154,12 @@ def owt_conv_bwd_data(desc, dy, y_or_null, w, dx, ws=None, stream=None):
                                   _stream(stream)))
 
 
+def owt_conv_bwd_data_relu_in(desc, dy, y_or_null, w, x, dx, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.owt_conv_bwd_data_relu_in(ctypes.byref(desc), _ptr(dy), _ptr(y_or_null), _ptr(w), _ptr(x), _ptr(dx),
+                                          p, n, _stream(stream)))
+
+
 def owt_conv_bwd_filter(desc, x, dy, y_or_null, alpha, beta, dw, dbias_or_null, ws=None, stream=None):
     p, n = _ws(ws)
     _check(_lib.owt_conv_bwd_filter(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(y_or_null), alpha, beta,
@@ -181,3 +190,8 @@ def owt_maxpool_fwd(N, H, W, C, win, stride, dtype, x, y, argmax, stream=None):
 
 def owt_maxpool_bwd(N, H, W, C, win, stride, dtype, dy, argmax, dx, stream=None):
     _check(_lib.owt_maxpool_bwd(N, H, W, C, win, stride, dtype, _ptr(dy), _ptr(argmax), _ptr(dx), _stream(stream)))
+
+
+def owt_maxpool_bwd_relu(N, H, W, C, win, stride, dtype, dy, argmax, y_pooled, dx, stream=None):
+    _check(_lib.owt_maxpool_bwd_relu(N, H, W, C, win, stride, dtype, _ptr(dy), _ptr(argmax), _ptr(y_pooled), _ptr(dx),
+                                     _stream(stream)))

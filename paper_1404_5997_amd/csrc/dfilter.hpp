@@ -1,0 +1,210 @@
+// Direct filter-gradient kernel for stride-1 "same" convolutions (P == H, Q == W), fp32 MFMA.
+//
+//   dw[k][r][s][c] = sum over pixels (n,p,q) of dz[n,p,q,k] * x[n, p+r-pad_h, q+s-pad_w, c]
+//
+// (Section 4 of the paper, backward step 2: the weight gradients of the
+// data-parallel convolution layers.)  A gather-style GEMM re-reads dz for every
+// 128 columns of (r,s,c) and x for every tap.  Here a work-group owns
+// 32*WK filters x 32*WC channels x ALL taps of a tap group and walks over the
+// pixels in chunks of 32: per chunk it loads the dz rows once and the x pixels
+// those 32 positions touch once, into LDS, laid out in ZERO-PADDED image
+// coordinates (Hp x Wp per image), where tap (r,s) of pixel (p,q) is simply
+// row ppad(p,q) + r*Wp + s: no bounds checks in the inner loop.  Each wavefront
+// keeps one 32 x 32 accumulator per tap (<= 9) and feeds all of them from one
+// dz fragment.
+//
+// Tap groups: all R*S taps at once when R*S == TAPS, else one filter row per
+// work-group when S == TAPS (the tap count is a compile-time constant so the
+// inner loop is branch-free; other filter sizes use the gather kernel).  The pixel range is split over blockIdx.y; partial sums are
+// reduced by splitk_reduce_kernel (deterministic, no atomics).
+#pragma once
+#include "igemm.hpp"
+
+namespace owt {
+
+template <class T, int WK, int WC, int TAPS, int PRF>
+__global__ void __launch_bounds__(64 * WK * WC, 2) dfilter_kernel(const GemmParams p)
+{
+    constexpr int NT = 64 * WK * WC, KT = 32 * WK, CT = 32 * WC, BP = 32;
+    constexpr int PA = KT + 4, PB = CT + 4;
+    constexpr int KQ = KT / 4, ARPP = NT / KQ, ANP = BP / ARPP;          // dz loader
+    constexpr int CQ = CT / 4, BRPP = NT / CQ, BNP = (PRF + BRPP - 1) / BRPP;   // x panel loader
+    static_assert(BP % ARPP == 0, "dz chunk must split evenly over the threads");
+
+    __shared__ __attribute__((aligned(16))) float dzs[BP * PA];
+    __shared__ __attribute__((aligned(16))) float panel[PRF * PB];
+    __shared__ int prow_tab[BP];
+
+    const Geom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int wk0 = (wave / WC) * 32, wc0 = (wave % WC) * 32;
+
+    const int ntiles = p.tiles_m * p.tiles_n;
+    const int b = blockIdx.x, xcd = b & 7;
+    const int logical = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + (b >> 3);
+    const int kt = logical / p.tiles_n, rem = logical - kt * p.tiles_n;
+    const int grp = rem / p.ctiles, ct = rem - grp * p.ctiles;
+    const int k0 = kt * KT, c0 = ct * CT;
+    const int split = blockIdx.y;
+    const int ch_beg = split * p.ksteps_per_split, ch_end = min(p.ksteps, ch_beg + p.ksteps_per_split);
+
+    const int RS = g.R * g.S, Wp = p.Wp, npix = p.Kd;
+    const int r0 = p.groups > 1 ? grp : 0, rows_g = p.groups > 1 ? 1 : g.R;
+    const int tap_first = p.groups > 1 ? grp * g.S : 0;
+
+    // padded linear index of the window's top-left corner of pixel pix
+    auto ppad = [&](int pix) {
+        const int n = g.dPQ.div(pix), pq = pix - n * g.P * g.Q;
+        const int pp = g.dQ.div(pq), q = pq - pp * g.Q;
+        return (n * p.Hp + pp) * Wp + q;
+    };
+
+    const T *dzsrc = (const T *)p.a, *xsrc = (const T *)p.b, *mask = (const T *)p.mask;
+    const int akq = tid % KQ, arow0 = tid / KQ;
+    const int bcq = tid % CQ, brow0 = tid / CQ;
+    float4 areg[ANP], breg[BNP];
+    int tab_next = 0;
+    const int pad_pix_total = g.N * p.Hp * Wp;
+
+    auto load_chunk = [&](int ch) {
+        const int pix0 = ch * BP;
+        const int ps = ppad(pix0) + r0 * Wp;
+        const int nrows = ppad(min(pix0 + BP, npix) - 1) + (r0 + rows_g - 1) * Wp + g.S - ps;   // <= PRF (host-checked)
+#pragma unroll
+        for (int i = 0; i < ANP; i++) {
+            const int pix = pix0 + arow0 + i * ARPP, k = k0 + akq * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (pix < npix && k < g.K) {
+                const int off = pix * g.K + k;
+                v = load4(dzsrc, off);
+                if (mask) {
+                    const float4 y = load4(mask, off);
+                    v.x = y.x > 0.f ? v.x : 0.f; v.y = y.y > 0.f ? v.y : 0.f;
+                    v.z = y.z > 0.f ? v.z : 0.f; v.w = y.w > 0.f ? v.w : 0.f;
+                }
+            }
+            areg[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < BNP; i++) {
+            const int row = brow0 + i * BRPP, idx = ps + row, c = c0 + bcq * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (row < nrows && idx < pad_pix_total && c < g.C) {
+                const int n = p.dHpWp.div(idx), r2 = idx - n * p.Hp * Wp;
+                const int hp = p.dWp.div(r2), wp = r2 - hp * Wp;
+                const int h = hp - g.ph, w = wp - g.pw;
+                if ((unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
+                    v = load4(xsrc, ((n * g.H + h) * g.W + w) * g.C + c);
+            }
+            breg[i] = v;
+        }
+        if (tid < BP) {
+            const int pix = pix0 + tid;
+            tab_next = pix < npix ? ppad(pix) + r0 * Wp - ps : 0;
+        }
+    };
+    auto store_chunk = [&]() {
+#pragma unroll
+        for (int i = 0; i < ANP; i++)
+            *(float4 *)(dzs + (arow0 + i * ARPP) * PA + akq * 4) = areg[i];
+#pragma unroll
+        for (int i = 0; i < BNP; i++) {
+            const int row = brow0 + i * BRPP;
+            if (row < PRF) *(float4 *)(panel + row * PB + bcq * 4) = breg[i];
+        }
+        if (tid < BP) prow_tab[tid] = tab_next;
+    };
+
+    float16v acc[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; t++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
+    int toff[TAPS];
+#pragma unroll
+    for (int t = 0; t < TAPS; t++) {
+        const int r = p.groups > 1 ? 0 : t / g.S, s = p.groups > 1 ? t : t - (t / g.S) * g.S;
+        toff[t] = (r * Wp + s) * PB + wc0 + li;
+    }
+
+    float4 dbacc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const bool do_db = ct == 0 && grp == 0 && p.dbias != nullptr;
+
+    if (ch_beg < ch_end) { load_chunk(ch_beg); store_chunk(); }
+    __syncthreads();
+
+    for (int ch = ch_beg; ch < ch_end; ch++) {
+        if (do_db) {
+#pragma unroll
+            for (int i = 0; i < ANP; i++) {
+                dbacc.x += areg[i].x; dbacc.y += areg[i].y; dbacc.z += areg[i].z; dbacc.w += areg[i].w;
+            }
+        }
+        const bool more = ch + 1 < ch_end;
+        if (more) load_chunk(ch + 1);
+        // fragments of pixel pair j+1 are fetched while the MFMAs of pair j run
+        float a_cur, b_cur[TAPS];
+        {
+            const int base = prow_tab[lh] * PB;
+            a_cur = dzs[lh * PA + wk0 + li];
+#pragma unroll
+            for (int t = 0; t < TAPS; t++) b_cur[t] = panel[base + toff[t]];
+        }
+#pragma unroll
+        for (int j = 0; j < BP / 2; j++) {
+            float a_nxt = 0.f, b_nxt[TAPS];
+            if (j + 1 < BP / 2) {
+                const int pix = 2 * (j + 1) + lh;
+                const int base = prow_tab[pix] * PB;
+                a_nxt = dzs[pix * PA + wk0 + li];
+#pragma unroll
+                for (int t = 0; t < TAPS; t++) b_nxt[t] = panel[base + toff[t]];
+            }
+#pragma unroll
+            for (int t = 0; t < TAPS; t++)
+                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b_cur[t], acc[t], 0, 0, 0);
+            if (j + 1 < BP / 2) {
+                a_cur = a_nxt;
+#pragma unroll
+                for (int t = 0; t < TAPS; t++) b_cur[t] = b_nxt[t];
+            }
+        }
+        __syncthreads();
+        if (more) store_chunk();
+        __syncthreads();
+    }
+
+    // ---- epilogue: dw[k][tap][c]; accumulator register r of lane (li, lh) holds
+    // filter k = 8*(r/4) + 4*lh + r%4 of the wavefront's 32, channel li.
+    const bool part = p.splits > 1;
+    float *pout = part ? p.partial + (size_t)split * p.M * p.Ncols : nullptr;
+    float *out = (float *)p.out;
+    const int c = c0 + wc0 + li;
+#pragma unroll
+    for (int t = 0; t < TAPS; t++) {
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int k = k0 + wk0 + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (k >= g.K || c >= g.C) continue;
+            const size_t o = ((size_t)k * RS + tap_first + t) * g.C + c;
+            if (part) pout[o] = acc[t][r];
+            else out[o] = p.alpha * acc[t][r] + (p.beta != 0.f ? p.beta * out[o] : 0.f);
+        }
+    }
+
+    if (do_db) {   // uniform over the work-group; every wave has passed the loop's last barrier
+        float *red = panel;
+        *(float4 *)(red + arow0 * KT + akq * 4) = dbacc;
+        __syncthreads();
+        if (tid < KT && k0 + tid < g.K) {
+            float s = 0.f;
+            for (int j = 0; j < ARPP; j++) s += red[j * KT + tid];
+            const int k = k0 + tid;
+            if (part) p.dbias_partial[(size_t)split * p.M + k] = s;
+            else p.dbias[k] = p.alpha * s + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);
+        }
+    }
+}
+
+}  // namespace owt

@@ -1,0 +1,40 @@
+// Instantiations of the direct filter-gradient kernel for one storage type.
+// Built twice: -DOWT_INST_BF16={0,1}.
+#include "dfilter.hpp"
+#include "owt_host.hpp"
+
+#ifndef OWT_INST_BF16
+#error "define OWT_INST_BF16 (0 fp32 storage, 1 bf16 storage)"
+#endif
+
+namespace owt {
+
+#if OWT_INST_BF16
+typedef bf16_t TT;
+#define OWT_FN owt_launch_dfilter_bf16
+#else
+typedef float TT;
+#define OWT_FN owt_launch_dfilter_f32
+#endif
+
+template <int WK, int WC, int TMAX, int PRF>
+static hipError_t go(const GemmParams &p, hipStream_t s)
+{
+    const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
+    hipLaunchKernelGGL((dfilter_kernel<TT, WK, WC, TMAX, PRF>), grid, dim3(64 * WK * WC), 0, s, p);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
+    return e;
+}
+
+hipError_t OWT_FN(int variant, const GemmParams &p, hipStream_t s)
+{
+    switch (variant) {
+    case 0: return go<4, 1, kDFilterVariants[0].tmax, kDFilterVariants[0].prf>(p, s);
+    case 1: return go<2, 2, kDFilterVariants[1].tmax, kDFilterVariants[1].prf>(p, s);
+    case 2: return go<2, 2, kDFilterVariants[2].tmax, kDFilterVariants[2].prf>(p, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace owt

@@ -230,10 +230,14 @@ template <class TOut_> struct EpiFwd {     // y = act(acc + bias)
         return v;
     }
 };
-template <class TOut_> struct EpiData {    // dx = acc
+template <class TOut_> struct EpiData {    // dx = acc, optionally zeroed where the layer's input is <= 0
     typedef TOut_ TOut;
     static constexpr bool DBIAS = false;
-    static __device__ __forceinline__ float op(const GemmParams &, int, int, float v) { return v; }
+    static __device__ __forceinline__ float op(const GemmParams &p, int row, int col, float v)
+    {
+        if (p.xmask && !(load1((const TOut *)p.xmask, row * p.Ncols + col) > 0.f)) v = 0.f;
+        return v;
+    }
 };
 struct EpiFilter {                         // dw = alpha*acc + beta*dw
     typedef float TOut;
@@ -531,16 +535,42 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) igemm_kernel(const GemmParams
 }
 
 // Sum the split-K partials and apply the epilogue: out[i] = op(sum_s partial[s][i]).
-template <class Epi>
+// The sum over splits always runs in the same order, so results are bit-identical run to run.
+// SG == 1: one thread per element (few splits, many elements).  SG == 8: eight threads per
+// element, each summing every eighth split, combined through LDS in a fixed order (many splits
+// of a small result, e.g. a filter gradient reduced over hundreds of work-groups).
+template <class Epi, int SG>
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p)
 {
     typedef typename Epi::TOut TOut;
     const size_t total = (size_t)p.M * p.Ncols;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        float s = 0.f;
-        for (int sp = 0; sp < p.splits; sp++) s += p.partial[(size_t)sp * total + i];
-        const int row = (int)(i / p.Ncols), col = (int)(i - (size_t)row * p.Ncols);
-        store1((TOut *)p.out, i, Epi::op(p, row, col, s));
+    if (SG == 1) {
+        for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
+            float s = 0.f;
+            for (int sp = 0; sp < p.splits; sp++) s += p.partial[(size_t)sp * total + i];
+            const int row = (int)(i / p.Ncols), col = (int)(i - (size_t)row * p.Ncols);
+            store1((TOut *)p.out, i, Epi::op(p, row, col, s));
+        }
+    } else {
+        __shared__ float red[SG][256 / SG];
+        constexpr int EPB = 256 / SG;                      // elements per block
+        const int e = threadIdx.x % EPB, sg = threadIdx.x / EPB;
+        for (size_t i0 = (size_t)blockIdx.x * EPB; i0 < total; i0 += (size_t)gridDim.x * EPB) {
+            const size_t i = i0 + e;
+            float s = 0.f;
+            if (i < total)
+                for (int sp = sg; sp < p.splits; sp += SG) s += p.partial[(size_t)sp * total + i];
+            red[sg][e] = s;
+            __syncthreads();
+            if (sg == 0 && i < total) {
+                float t = 0.f;
+#pragma unroll
+                for (int j = 0; j < SG; j++) t += red[j][e];
+                const int row = (int)(i / p.Ncols), col = (int)(i - (size_t)row * p.Ncols);
+                store1((TOut *)p.out, i, Epi::op(p, row, col, t));
+            }
+            __syncthreads();
+        }
     }
     if (Epi::DBIAS && p.dbias) {
         for (int k = blockIdx.x * 256 + threadIdx.x; k < p.M; k += gridDim.x * 256) {
@@ -549,6 +579,22 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p)
             p.dbias[k] = p.alpha * s + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);
         }
     }
+}
+
+template <class Epi>
+static inline hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s)
+{
+    const size_t total = (size_t)p.M * p.Ncols;
+    if (p.splits >= 16) {
+        size_t blocks = (total + 31) / 32;
+        if (blocks > 65536) blocks = 65536;
+        hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 8>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+    } else {
+        size_t blocks = (total + 255) / 256;
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+    }
+    return hipGetLastError();
 }
 
 }  // namespace owt

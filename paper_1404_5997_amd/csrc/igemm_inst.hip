@@ -37,13 +37,7 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
     hipLaunchKernelGGL((igemm_kernel<OA, OB, OE, VA, VB, WM, WN, BK>), grid, dim3(64 * WM * WN), 0, s, p);
     hipError_t e = hipGetLastError();
-    if (e == hipSuccess && p.splits > 1) {
-        const size_t total = (size_t)p.M * p.Ncols;
-        int blocks = (int)((total + 255) / 256);
-        if (blocks > 2048) blocks = 2048;
-        hipLaunchKernelGGL((splitk_reduce_kernel<OE>), dim3(blocks), dim3(256), 0, s, p);
-        e = hipGetLastError();
-    }
+    if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<OE>(p, s);
     return e;
 }
 

@@ -5,6 +5,7 @@
 #include <vector>
 
 #include "owt_host.hpp"
+#include "sfilter.hpp"
 
 namespace owt {
 
@@ -47,7 +48,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -95,8 +96,45 @@ static long direct_panel_rows(const Geom &g, int pass, const PassDims &dm)
     return need;
 }
 
+// Tap grouping and panel size of the direct filter-gradient kernel for one variant; false when it
+// does not apply (needs stride 1, P == H, Q == W, C and K multiples of 4, R*S or S equal to the variant's tap count, and a
+// 32-pixel chunk whose padded-coordinate span fits the variant's LDS panel).
+static bool dfilter_fits(const Geom &g, int variant, int &taps, int &groups)
+{
+    const DFilterVariant &v = kDFilterVariants[variant];
+    if (g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W || g.C % 4 || g.K % 4) return false;
+    if (g.R * g.S == v.tmax) { taps = g.R * g.S; groups = 1; }
+    else if (g.S == v.tmax) { taps = g.S; groups = g.R; }
+    else return false;
+    const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q;
+    const long span = 31 + (31 / g.Q + 1) * (Wp - g.Q) + (31 / PQ + 1) * (Hp - g.P) * Wp;
+    const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
+    return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
+}
+
+// Geometry of the small-channel strided filter-gradient kernel; false when it does not apply
+// (needs window starts and image rows that are multiples of 4 floats, at most 14 blocks of 32
+// slots, and an LDS footprint that leaves room for two work-groups per CU).
+static bool sfilter_geom(const Geom &g, SFilterGeom &sg)
+{
+    if ((g.sw * g.C) % 4 || (g.W * g.C) % 4 || g.K % 4) return false;
+    sg.SEG = g.S * g.C;
+    sg.LPAD = (4 - (g.pw * g.C) % 4) % 4;
+    sg.SLOTS = (sg.SEG + sg.LPAD + 3) & ~3;
+    const int a = g.pw * g.C + sg.LPAD + g.W * g.C, b = (g.Q - 1) * g.sw * g.C + sg.SLOTS;
+    sg.PITCH = ((a > b ? a : b) + 3) & ~3;
+    sg.ROWS = g.sh + g.R;                         // two output rows
+    sg.NB = (g.R * sg.SLOTS + 31) / 32;
+    sg.DZP = (2 * g.Q + 1) & ~1;
+    sg.units_per_image = (g.P + 1) / 2;
+    sg.units = g.N * sg.units_per_image;
+    const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
+    return sg.NB <= 14 && lds <= 78 * 1024 && g.C <= 16 &&
+           (long)sg.ROWS * (g.W * g.C / 4) <= 256L * kSFilterPNP && (long)sg.DZP * 16 <= 256L * kSFilterDNP;
+}
+
 struct Launch {
-    int kind, tile, splits, steps, steps_per_split, tiles_m, tiles_n, pr;
+    int kind, tile, splits, steps, steps_per_split, tiles_m, tiles_n, pr, taps, groups, ctiles;
     size_t partial_bytes, dbias_bytes;
     double cost;   // model estimate, ~clocks
     size_t ws_bytes() const { return partial_bytes + dbias_bytes; }
@@ -163,7 +201,63 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             }
         }
     }
-    const bool have_direct = !out.empty();      // the gather kernel is only the fallback
+    SFilterGeom sfg;
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct && (g.sh > 1 || g.sw > 1) && sfilter_geom(g, sfg)) {
+        const long ktiles = cdiv(g.K, 64);
+        for (long target : {256L, 512L, 1024L}) {
+            long wgs = target / ktiles > 0 ? target / ktiles : 1;
+            if (force_split > 0) wgs = force_split;
+            if (wgs > sfg.units) wgs = sfg.units;
+            const long per = cdiv(sfg.units, wgs), splits = cdiv(sfg.units, per);
+            Launch l; memset(&l, 0, sizeof(l));
+            l.kind = KIND_SFILTER; l.tile = 0; l.splits = (int)splits; l.steps = sfg.units; l.steps_per_split = (int)per;
+            l.tiles_m = (int)ktiles; l.tiles_n = 1;
+            if (splits > 1) {
+                l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+            }
+            l.cost = model_cost(ktiles * splits, 4, 2, 64.0 * sfg.NB * 32 * sfg.DZP * per, 1.0, splits, dm.M, dm.Ncols);
+            bool dup = false;
+            for (const Launch &o : out) dup |= o.kind == l.kind && o.splits == l.splits;
+            if (!dup) out.push_back(l);
+            if (force_split > 0) break;
+        }
+    }
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct) {
+        for (int v = 0; v < 3; v++) {
+            int taps, groups;
+            if (force_tile >= 0 && force_tile != v) continue;
+            if (!dfilter_fits(g, v, taps, groups)) continue;
+            if (v == 2 && g.K % 128 == 0) continue;                  // variant 0 covers it with the same accumulators
+            const DFilterVariant &dv = kDFilterVariants[v];
+            const long KT = 32 * dv.WK, CT = 32 * dv.WC;
+            const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, 32);
+            for (long s0 : kSplits) {
+                long s = s0;
+                if (force_split > 0) s = force_split < steps ? force_split : steps;
+                else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 2560)) break;
+                const long per = cdiv(steps, s), splits = cdiv(steps, per);
+                Launch l; memset(&l, 0, sizeof(l));
+                l.kind = KIND_DFILTER; l.tile = v; l.splits = (int)splits; l.steps = (int)steps;
+                l.steps_per_split = (int)per; l.tiles_m = (int)tm; l.tiles_n = (int)(ctl * groups);
+                l.taps = taps; l.groups = groups; l.ctiles = (int)ctl;
+                if (splits > 1) {
+                    l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                    l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+                }
+                l.cost = model_cost(tm * ctl * groups * splits, 4, 2, (double)KT * CT * 32 * taps * per, 1.2, splits,
+                                    dm.M, dm.Ncols);
+                bool dup = false;
+                for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
+                if (!dup && (l.partial_bytes <= kMaxPartialBytes || force_split > 0) &&
+                    (force_split > 0 || tm * ctl * groups * splits >= 128 || s0 == 256)) out.push_back(l);
+                if (force_split > 0) break;
+            }
+        }
+    }
+    // the gather kernel is the fallback of the stride-1 forward / backward-data kernel, and an
+    // alternative worth timing next to the direct filter-gradient kernel
+    const bool have_direct = !out.empty() && out[0].kind == KIND_DIRECT;
     for (int t = 0; t < NUM_TILES && !have_direct; t++) {
         if (!vec && t != TILE_64x64) continue;
         if (vec && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
@@ -188,7 +282,10 @@ static PlanKey plan_key(const Geom &g, int pass, owt_dtype dt)
     return PlanKey{g.N, g.C, g.H, g.W, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, pass, (int)dt, 0, 0};
 }
 
-static bool env_overrides() { return getenv("OWT_TILE") || getenv("OWT_SPLITK") || getenv("OWT_NO_DIRECT"); }
+static bool env_overrides()
+{
+    return getenv("OWT_TILE") || getenv("OWT_SPLITK") || getenv("OWT_NO_DIRECT") || getenv("OWT_ONLY_DIRECT");
+}
 
 static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, bool want_db, bool use_cache)
 {
@@ -199,9 +296,13 @@ static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, 
     }
     std::vector<Launch> c;
     enumerate(g, pass, dm, want_db, c);
-    size_t best = 0;
-    for (size_t i = 1; i < c.size(); i++)
-        if (c[i].cost < c[best].cost) best = i;
+    bool only_direct = getenv("OWT_ONLY_DIRECT") != nullptr, any_direct = false;   // test hook
+    for (const Launch &l : c) any_direct |= l.kind != KIND_GATHER;
+    size_t best = c.size();
+    for (size_t i = 0; i < c.size(); i++) {
+        if (only_direct && any_direct && c[i].kind == KIND_GATHER) continue;
+        if (best == c.size() || c[i].cost < c[best].cost) best = i;
+    }
     return c[best];
 }
 
@@ -225,7 +326,16 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
     p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.partial_bytes) : nullptr;
     const bool bf = dt == OWT_BF16;
     hipError_t e;
-    if (l.kind == KIND_DIRECT) {
+    if (l.kind == KIND_SFILTER) {
+        SFilterGeom sg;
+        sfilter_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        e = bf ? owt_launch_sfilter_bf16(p, sg, l.tiles_m, s) : owt_launch_sfilter_f32(p, sg, l.tiles_m, s);
+    } else if (l.kind == KIND_DFILTER) {
+        p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
+        p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
+        e = bf ? owt_launch_dfilter_bf16(l.tile, p, s) : owt_launch_dfilter_f32(l.tile, p, s);
+    } else if (l.kind == KIND_DIRECT) {
         dconv_frame(g, pass, p);
         if (pass == OWT_PASS_FWD) e = bf ? owt_launch_dconv_fwd_bf16(l.tile, l.pr, p, s) : owt_launch_dconv_fwd_f32(l.tile, l.pr, p, s);
         else e = bf ? owt_launch_dconv_data_bf16(l.tile, l.pr, p, s) : owt_launch_dconv_data_f32(l.tile, l.pr, p, s);
@@ -244,6 +354,13 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
 static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims &dm, const Launch &l)
 {
     static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
+    if (l.kind == KIND_SFILTER)
+        return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d", pn[pass], dt == OWT_BF16 ? "bf16" : "f32",
+                        l.splits, l.tiles_m, l.splits);
+    if (l.kind == KIND_DFILTER)
+        return snprintf(buf, n, "dfilter %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d", pn[pass],
+                        dt == OWT_BF16 ? "bf16" : "f32", 32 * kDFilterVariants[l.tile].WK, 32 * kDFilterVariants[l.tile].WC,
+                        l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits);
     const TileInfo &ti = kTiles[l.tile];
     if (l.kind == KIND_DIRECT)
         return snprintf(buf, n, "dconv %s %s tile128x%dx%d panel%d splitk%d grid%dx%d", pn[pass],
@@ -308,10 +425,11 @@ static GemmParams fwd_params(const owt_conv_desc *d, const void *x, const void *
     p.a = x; p.b = w; p.out = y; p.bias = bias; p.flags = d->flags;
     return p;
 }
-static GemmParams data_params(const owt_conv_desc *d, const void *dy, const void *y, const void *w, void *dx)
+static GemmParams data_params(const owt_conv_desc *d, const void *dy, const void *y, const void *w, void *dx,
+                              const void *xmask = nullptr)
 {
     GemmParams p; memset(&p, 0, sizeof(p));
-    p.a = dy; p.b = w; p.out = dx; p.flags = d->flags;
+    p.a = dy; p.b = w; p.out = dx; p.flags = d->flags; p.xmask = xmask;
     p.mask = (d->flags & OWT_RELU) ? y : nullptr;
     return p;
 }
@@ -409,6 +527,18 @@ owt_status owt_conv_bwd_data(const owt_conv_desc *d, const void *dy, const void 
     OWT_TRY(check_ptr(dy, "dy")); OWT_TRY(check_ptr(w, "w")); OWT_TRY(check_ptr(dx, "dx"));
     if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
     return conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, data_params(d, dy, y_or_null, w, dx), false, ws, ws_bytes,
+                     (hipStream_t)hip_stream, true);
+}
+
+owt_status owt_conv_bwd_data_relu_in(const owt_conv_desc *d, const void *dy, const void *y_or_null,
+                                     const void *w, const void *x, void *dx, void *ws, size_t ws_bytes,
+                                     void *hip_stream)
+{
+    Geom g;
+    OWT_TRY(check_conv(d, g));
+    OWT_TRY(check_ptr(dy, "dy")); OWT_TRY(check_ptr(w, "w")); OWT_TRY(check_ptr(dx, "dx")); OWT_TRY(check_ptr(x, "x"));
+    if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
+    return conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, data_params(d, dy, y_or_null, w, dx, x), false, ws, ws_bytes,
                      (hipStream_t)hip_stream, true);
 }
 

@@ -36,6 +36,7 @@ struct GemmParams {
     int M, Ncols, Kd;        // GEMM extents of this pass
     const void *a, *b;       // tensors the A and B operands are gathered from
     const void *mask;        // forward output y (ReLU mask of the dz operand) or null
+    const void *xmask;       // bwd-data only: the layer's input; dx is zeroed where it is <= 0 (or null)
     void *out;               // result tensor (used when splits == 1)
     float *partial;          // [splits][M][Ncols] fp32 (used when splits > 1)
     const float *bias;       // forward epilogue
@@ -50,6 +51,11 @@ struct GemmParams {
     // (ho-pah+r, wo-paw+s), r < R, s < S.
     int Hi, Wi, Ho, Wo, pah, paw, Cred;
     FastDiv dWo, dHoWo;
+    // Direct filter-gradient kernel only: the input seen in zero-padded coordinates
+    // (Hp = H + 2*pad_h rows of Wp = W + 2*pad_w pixels per image); taps are handled
+    // `taps` at a time, either all R*S at once (groups == 1) or one filter row per group.
+    int Hp, Wp, taps, groups, ctiles;
+    FastDiv dWp, dHpWp;
 };
 
 struct bf16_t { uint16_t bits; };

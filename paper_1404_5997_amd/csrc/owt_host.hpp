@@ -37,4 +37,16 @@ hipError_t owt_launch_dconv_fwd_bf16(int tile, int pr, const GemmParams &, hipSt
 hipError_t owt_launch_dconv_data_f32(int tile, int pr, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dconv_data_bf16(int tile, int pr, const GemmParams &, hipStream_t);
 
+// Direct filter-gradient kernel (dfilter_inst.hip): wavefront grid WK x WC (32 filters x 32
+// channels each), exactly tmax taps per work-group, LDS panel of prf padded-image pixels.
+struct DFilterVariant { int WK, WC, tmax, prf; };
+constexpr DFilterVariant kDFilterVariants[3] = {{4, 1, 9, 128}, {2, 2, 5, 192}, {2, 2, 9, 128}};
+hipError_t owt_launch_dfilter_f32(int variant, const GemmParams &, hipStream_t);
+hipError_t owt_launch_dfilter_bf16(int variant, const GemmParams &, hipStream_t);
+
+// Small-channel strided filter-gradient kernel (sfilter_inst.hip).
+struct SFilterGeom;
+hipError_t owt_launch_sfilter_f32(const GemmParams &, const SFilterGeom &, int ktiles, hipStream_t);
+hipError_t owt_launch_sfilter_bf16(const GemmParams &, const SFilterGeom &, int ktiles, hipStream_t);
+
 }  // namespace owt

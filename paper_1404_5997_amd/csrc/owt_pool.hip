@@ -37,7 +37,8 @@ __global__ void __launch_bounds__(256) maxpool_fwd_kernel(const T *__restrict__ 
 
 template <class T, int V>
 __global__ void __launch_bounds__(256) maxpool_bwd_kernel(const T *__restrict__ dy,
-                                                          const unsigned char *__restrict__ am, T *__restrict__ dx,
+                                                          const unsigned char *__restrict__ am,
+                                                          const T *__restrict__ yp, T *__restrict__ dx,
                                                           int N, int H, int W, int C, int win, int st, int P, int Q,
                                                           FastDiv dCv, FastDiv dW, FastDiv dH, FastDiv dst)
 {
@@ -61,13 +62,18 @@ __global__ void __launch_bounds__(256) maxpool_bwd_kernel(const T *__restrict__ 
                 const int off = ((n * P + p) * Q + q) * C + c;
                 if constexpr (V == 4) {
                     const uint32_t a4 = *(const uint32_t *)(am + off);
-                    const float4 g = load4(dy, off);
+                    float4 g = load4(dy, off);
+                    if (yp) {   // fused ReLU backward: a window whose maximum is <= 0 passes nothing
+                        const float4 y = load4(yp, off);
+                        g.x = y.x > 0.f ? g.x : 0.f; g.y = y.y > 0.f ? g.y : 0.f;
+                        g.z = y.z > 0.f ? g.z : 0.f; g.w = y.w > 0.f ? g.w : 0.f;
+                    }
                     if ((int)(a4 & 255u) == code) acc[0] += g.x;
                     if ((int)((a4 >> 8) & 255u) == code) acc[1] += g.y;
                     if ((int)((a4 >> 16) & 255u) == code) acc[2] += g.z;
                     if ((int)(a4 >> 24) == code) acc[3] += g.w;
                 } else if ((int)am[off] == code) {
-                    acc[0] += load1(dy, off);
+                    if (!yp || load1(yp, off) > 0.f) acc[0] += load1(dy, off);
                 }
             }
         const size_t o = (size_t)pix * C + c;
@@ -118,8 +124,8 @@ owt_status owt_maxpool_fwd(int N, int H, int W, int C, int win, int stride, owt_
     return OWT_OK;
 }
 
-owt_status owt_maxpool_bwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
-                           const void *dy, const unsigned char *argmax, void *dx, void *hip_stream)
+static owt_status pool_bwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype, const void *dy,
+                           const unsigned char *argmax, const void *yp, void *dx, void *hip_stream)
 {
     int P, Q;
     owt_status st = check_pool(N, H, W, C, win, stride, dtype, P, Q);
@@ -131,13 +137,27 @@ owt_status owt_maxpool_bwd(int N, int H, int W, int C, int win, int stride, owt_
     const long total = (long)N * H * W * (C / V);
     hipStream_t s = (hipStream_t)hip_stream;
 #define OWT_POOL_B(T, VV) hipLaunchKernelGGL((maxpool_bwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \
-        (const T *)dy, argmax, (T *)dx, N, H, W, C, win, stride, P, Q, dCv, dW, dH, dst)
+        (const T *)dy, argmax, (const T *)yp, (T *)dx, N, H, W, C, win, stride, P, Q, dCv, dW, dH, dst)
     if (dtype == OWT_F32) { if (V == 4) OWT_POOL_B(float, 4); else OWT_POOL_B(float, 1); }
     else { if (V == 4) OWT_POOL_B(bf16_t, 4); else OWT_POOL_B(bf16_t, 1); }
 #undef OWT_POOL_B
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(OWT_ELAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
     return OWT_OK;
+}
+
+owt_status owt_maxpool_bwd(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                           const void *dy, const unsigned char *argmax, void *dx, void *hip_stream)
+{
+    return pool_bwd(N, H, W, C, win, stride, dtype, dy, argmax, nullptr, dx, hip_stream);
+}
+
+owt_status owt_maxpool_bwd_relu(int N, int H, int W, int C, int win, int stride, owt_dtype dtype,
+                                const void *dy, const unsigned char *argmax, const void *y_pooled, void *dx,
+                                void *hip_stream)
+{
+    if (!y_pooled || !aligned16(y_pooled)) return fail(OWT_EINVAL, "y_pooled is NULL or misaligned");
+    return pool_bwd(N, H, W, C, win, stride, dtype, dy, argmax, y_pooled, dx, hip_stream);
 }
 
 }  // extern "C"

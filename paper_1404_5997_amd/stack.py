@@ -13,8 +13,8 @@ build.
 import torch
 
 from . import (OWT_BF16, OWT_BIAS, OWT_F32, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER, OWT_PASS_FWD, OWT_RELU,
-               conv_desc, fc_desc, owt_conv_autotune, owt_conv_bwd_data, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
-               owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_maxpool_bwd, owt_maxpool_fwd)
+               conv_desc, fc_desc, owt_conv_autotune, owt_conv_bwd_data, owt_conv_bwd_data_relu_in, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
+               owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_maxpool_bwd_relu, owt_maxpool_fwd)
 
 
 class ConvStack:
@@ -36,7 +36,7 @@ class ConvStack:
             K, R, st, pad = spec["K"], spec["R"], spec["stride"], spec["pad"]
             d = conv_desc(N, C, H, W, K, R, R, st, pad, self.code, OWT_BIAS | OWT_RELU)
             P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - R) // st + 1
-            e = dict(desc=d, geom=(N, C, H, W, K, R, st, pad, P, Q), pool=spec["pool"],
+            e = dict(desc=d, desc_bwd=conv_desc(N, C, H, W, K, R, R, st, pad, self.code, OWT_BIAS), geom=(N, C, H, W, K, R, st, pad, P, Q), pool=spec["pool"],
                      w=torch.empty((K, R, R, C), device=dev, dtype=self.tdt),
                      b=torch.empty((K,), device=dev, dtype=torch.float32),
                      y=torch.empty((N, P, Q, K), device=dev, dtype=self.tdt),
@@ -54,6 +54,8 @@ class ConvStack:
                 H, W = PP, QQ
             self.L.append(e)
         self.out_shape = (N, H, W, C)
+        for li, e in enumerate(self.L):   # does someone upstream of the layer's backward apply its ReLU mask?
+            e["dz_ready"] = bool(e["pool"]) or li + 1 < len(self.L)
         # the gradient w.r.t. a layer's output lives in that layer's dy (no pool) or da (pool)
         self.F = []
         if fc_layers:
@@ -144,17 +146,24 @@ class ConvStack:
             e = self.L[li]
             N, C, H, W, K, R, st, pad, P, Q = e["geom"]
             if e["pool"]:
-                self._run("pool%d bwd" % (li + 1), owt_maxpool_bwd, N, P, Q, K, self.win, self.pst, self.code, e["da"], e["am"], e["dy"])
-            self._run("conv%d bwd_filter" % (li + 1), owt_conv_bwd_filter, e["desc"], e["x"], e["dy"], e["y"], self.alpha, self.beta,
+                self._run("pool%d bwd" % (li + 1), owt_maxpool_bwd_relu, N, P, Q, K, self.win, self.pst, self.code,
+                          e["da"], e["am"], e["a"], e["dy"])
+            # e["dy"] already holds dz = dy*[y > 0] when its producer applied the ReLU mask
+            # (the fused pooling backward above, or the next layer's bwd-data below)
+            d, ymask = (e["desc_bwd"], None) if e["dz_ready"] else (e["desc"], e["y"])
+            self._run("conv%d bwd_filter" % (li + 1), owt_conv_bwd_filter, d, e["x"], e["dy"], ymask, self.alpha, self.beta,
                       e["dw"], e["db"], self.ws)
             if li > 0:
                 prev = self.L[li - 1]
-                self._run("conv%d bwd_data" % (li + 1), owt_conv_bwd_data, e["desc"], e["dy"], e["y"], e["w"],
-                          prev["da"] if prev["pool"] else prev["dy"], self.ws)
+                if prev["pool"]:
+                    self._run("conv%d bwd_data" % (li + 1), owt_conv_bwd_data, d, e["dy"], ymask, e["w"], prev["da"], self.ws)
+                else:   # prev's output feeds this layer directly: fuse prev's ReLU backward into the store
+                    self._run("conv%d bwd_data" % (li + 1), owt_conv_bwd_data_relu_in, d, e["dy"], ymask, e["w"], e["x"],
+                              prev["dy"], self.ws)
             elif not self.skip_first_dx:
                 if "dx0" not in e:
                     e["dx0"] = torch.empty_like(self.x)
-                self._run("conv1 bwd_data", owt_conv_bwd_data, e["desc"], e["dy"], e["y"], e["w"], e["dx0"], self.ws)
+                self._run("conv1 bwd_data", owt_conv_bwd_data, d, e["dy"], ymask, e["w"], e["dx0"], self.ws)
 
     def step(self):
         self.forward()
@@ -167,11 +176,11 @@ class ConvStack:
         for li, e in enumerate(self.L):
             prev = self.L[li - 1] if li > 0 else None
             dx = (prev["da"] if prev["pool"] else prev["dy"]) if prev is not None else None
+            d = e["desc_bwd"] if e["dz_ready"] else e["desc"]
             owt_conv_autotune(e["desc"], OWT_PASS_FWD, e["x"], e["w"], e["b"], e["y"], None, None, None, None, self.ws)
             if dx is not None:
-                owt_conv_autotune(e["desc"], OWT_PASS_BWD_DATA, None, e["w"], None, e["y"], e["dy"], dx, None, None, self.ws)
-            owt_conv_autotune(e["desc"], OWT_PASS_BWD_FILTER, e["x"], e["w"], None, e["y"], e["dy"], None, e["dw"],
-                              e["db"], self.ws)
+                owt_conv_autotune(d, OWT_PASS_BWD_DATA, None, e["w"], None, e["y"], e["dy"], dx, None, None, self.ws)
+            owt_conv_autotune(d, OWT_PASS_BWD_FILTER, e["x"], e["w"], None, e["y"], e["dy"], None, e["dw"], e["db"], self.ws)
         self.step()
 
     # ----------------------------------------------------------- work counters

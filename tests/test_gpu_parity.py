@@ -127,7 +127,7 @@ def test_flags_and_scaling_variants():
 
 
 @pytest.mark.parametrize("tile,split,direct", [(0, 1, 0), (1, 1, 0), (2, 1, 0), (3, 1, 0), (0, 3, 0), (1, 4, 0),
-                                               (2, 2, 0), (3, 8, 0), (0, 1, 1), (1, 1, 1), (0, 2, 1), (1, 3, 1)])
+                                               (2, 2, 0), (3, 8, 0), (0, 1, 1), (1, 1, 1), (0, 2, 1), (1, 3, 1), (2, 5, 1)])
 def test_every_tile_shape_and_split_k(tile, split, direct):
     # The planner is overridden so each instantiation of the gather kernel (direct = 0) and of the
     # panel-resident stride-1 kernel (direct = 1), and the two-pass split reduction, are exercised.
@@ -143,6 +143,26 @@ def test_every_tile_shape_and_split_k(tile, split, direct):
             layer_parity(2, 8, 12, 12, 8, 3, 3, 1, 0, seed=88 + tile)        # pad 0: forward direct, bwd-data gathers
     finally:
         for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_DIRECT"):
+            os.environ.pop(k, None)
+
+
+@pytest.mark.parametrize("shape,split", [
+    ((5, 4, 23, 20, 8, 7, 7, 4, 2), 3), ((2, 3, 24, 24, 72, 7, 7, 4, 3), 0), ((3, 3, 36, 28, 64, 11, 11, 4, 2), 5),
+    ((2, 8, 17, 12, 20, 5, 3, (2, 2), (2, 1)), 2), ((2, 3, 224, 224, 64, 11, 11, 4, 2), 0)])
+def test_strided_small_channel_filter_gradient_kernel(shape, split):
+    # first-layer style geometry: the row-panel filter-gradient kernel, forced, with and without a split
+    m = owt()
+    N, C, H, W, K, R, S, stride, pad = shape
+    os.environ["OWT_ONLY_DIRECT"] = "1"
+    if split:
+        os.environ["OWT_SPLITK"] = str(split)
+    try:
+        d = m.conv_desc(N, C, H, W, K, R, S, stride, pad, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
+        assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("sfilter")
+        layer_parity(N, C, H, W, K, R, S, stride, pad, seed=200 + split)
+        layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, alpha=0.25, beta=1.0, seed=210 + split)
+    finally:
+        for k in ("OWT_ONLY_DIRECT", "OWT_SPLITK"):
             os.environ.pop(k, None)
 
 
@@ -296,6 +316,45 @@ def test_maxpool_parity(N, H, W, C, win, st, dt):
     m.owt_maxpool_bwd(N, H, W, C, win, st, code, to_dev(dy, dt), to_dev(am_ref), dx)
     torch.cuda.synchronize()
     assert_close(to_host(dx), dx_ref, dt, "maxpool bwd")
+
+
+def test_fused_relu_backward_entry_points():
+    # owt_maxpool_bwd_relu == mask(pool_bwd(dy)) and owt_conv_bwd_data_relu_in == mask(bwd_data(dy)),
+    # the mask being [input of the ReLU's consumer > 0]; oracle = the unfused definition.
+    m = owt()
+    g = np.random.default_rng(314)
+    for dt in ("f32", "bf16"):
+        N, H, W, C, win, st = 3, 13, 13, 24, 3, 2
+        y = prep(np.maximum(g.standard_normal((N, H, W, C), dtype=np.float32), 0), dt)      # a ReLU output
+        a_ref, am_ref = oracle.maxpool_fwd(y, win, st)
+        P, Q = a_ref.shape[1:3]
+        da = prep(g.standard_normal((N, P, Q, C), dtype=np.float32), dt)
+        ref = oracle.maxpool_bwd(da, am_ref, (H, W), win, st) * (y > 0)
+        ref = oracle.round_bf16(ref) if dt == "bf16" else ref
+        dx = empty((N, H, W, C), dt)
+        code = m.OWT_BF16 if dt == "bf16" else m.OWT_F32
+        m.owt_maxpool_bwd_relu(N, H, W, C, win, st, code, to_dev(da, dt), to_dev(am_ref), to_dev(a_ref, dt), dx)
+        torch.cuda.synchronize()
+        assert_close(to_host(dx), ref, dt, "maxpool_bwd_relu")
+        assert (ref[y <= 0] == 0).all() and np.count_nonzero(a_ref <= 0) > 0       # the mask really bites
+
+        for (K, split) in ((40, None), (136, "3")):
+            case = ConvCase(4, 24, 13, 13, K, 3, 3, 1, 1, dt, True, True)
+            x = prep(np.maximum(g.standard_normal(case.shape_x, dtype=np.float32), 0), dt)
+            w = prep(g.standard_normal(case.shape_w, dtype=np.float32) * np.float32(0.05), dt)
+            yy = prep(g.standard_normal(case.shape_y, dtype=np.float32), dt)
+            dy = prep(g.standard_normal(case.shape_y, dtype=np.float32), dt)
+            ref = oracle.conv_bwd_data(dy, w, (13, 13), 1, 1, y=yy) * (x > 0)
+            ref = oracle.round_bf16(ref) if dt == "bf16" else ref
+            out = empty(case.shape_x, dt)
+            if split:
+                os.environ["OWT_SPLITK"] = split
+            try:
+                m.owt_conv_bwd_data_relu_in(case.desc, to_dev(dy, dt), to_dev(yy, dt), to_dev(w, dt), to_dev(x, dt), out, case.ws(1))
+            finally:
+                os.environ.pop("OWT_SPLITK", None)
+            torch.cuda.synchronize()
+            assert_close(to_host(out), ref, dt, "conv_bwd_data_relu_in K=%d" % K)
 
 
 # -------------------------------------------------------------- error paths ----

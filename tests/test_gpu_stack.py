@@ -9,7 +9,7 @@ The whole batch runs on the GPU.  The oracle cannot redo 485 GFLOP in a test, so
    oracle's pooling of the GPU's own convolution output (all images);
  * backward-data: the oracle back-propagates the same upstream gradient through
    the same images, using the GPU's forward outputs as ReLU masks and the GPU's
-   arg-max (both just shown valid), and every layer's dx is compared.  ReLU and
+   arg-max (both just shown valid), and every layer's dz (and dx) is compared.  ReLU and
    arg-max are not smooth, so an element that is +1e-9 on one side and 0 on the
    other would otherwise move gradients by far more than rounding; feeding both
    sides the same mask makes every backward call a pure function of its inputs;
@@ -91,22 +91,27 @@ def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, n_sub, n_dw_samples=96):
         del y_gpu, a_ref, am_ref
     say("  pooled maxima and arg-max exact on all images")
 
-    # ---- backward-data chain on the first n_sub images, GPU masks / arg-max as inputs
+    # ---- backward chain on the first n_sub images, GPU masks / arg-max as inputs.  The stack applies
+    # each layer's ReLU mask where the gradient w.r.t. that layer's output is PRODUCED (fused into the
+    # pooling backward, or into the store of the next layer's bwd-data), so every e["dy"] holds
+    # dz = dy * [y > 0]; the oracle applies the mask as its own elementwise step.
     g = dtop_pooled[sub]
     for li in range(len(st.L) - 1, -1, -1):
         e, spec = st.L[li], si.STACK_LAYERS[li]
         Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+        y_mask = to_host(e["y"][sub])
         if spec["pool"]:
             g = rnd(oracle.maxpool_bwd(g, e["am"][sub].cpu().numpy(), (P, Q), win, pst))
-            assert_close(to_host(e["dy"][sub]), g, dt, "pool%d bwd" % (li + 1))
+        assert e["dz_ready"]
+        dz = g * (y_mask > 0)
+        err = assert_close(to_host(e["dy"][sub]), dz, dt, "conv%d dz" % (li + 1))
         if li == 0:
             break
-        y_mask = to_host(e["y"][sub])
-        g = rnd(oracle.conv_bwd_data(g, ws[li], (H, W), stv, pad, y=y_mask))
+        g = rnd(oracle.conv_bwd_data(dz, ws[li], (H, W), stv, pad))
         prev = st.L[li - 1]
-        got = to_host((prev["da"] if prev["pool"] else prev["dy"])[sub])
-        err = assert_close(got, g, dt, "conv%d bwd_data" % (li + 1))
-        say("  conv%d bwd_data rel err %.2e" % (li + 1, err))
+        if prev["pool"]:
+            err = assert_close(to_host(prev["da"][sub]), g, dt, "conv%d bwd_data" % (li + 1))
+        say("  conv%d dz rel err %.2e" % (li + 1, err))
 
     # ---- backward-filter: sampled dw entries and all of db from the GPU's full-batch call inputs
     rs = np.random.default_rng(123)
@@ -116,7 +121,7 @@ def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, n_sub, n_dw_samples=96):
         idx = np.stack([rs.integers(0, K, n_dw_samples), rs.integers(0, R, n_dw_samples),
                         rs.integers(0, R, n_dw_samples), rs.integers(0, C, n_dw_samples)], axis=1).astype(np.int32)
         idx[0] = (0, 0, 0, 0); idx[1] = (K - 1, R - 1, R - 1, C - 1)
-        ref = oracle.conv_bwd_filter_at(xin, dyin, idx, (R, R), stv, pad, y=yin).astype(np.float64) * st.alpha
+        ref = oracle.conv_bwd_filter_at(xin, dyin, idx, (R, R), stv, pad).astype(np.float64) * st.alpha   # dyin is dz
         dw = e["dw"].cpu().numpy()
         got = dw[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
         scale = np.max(np.abs(dw))          # the tensor's max norm (the sample need not contain it)
@@ -125,7 +130,7 @@ def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, n_sub, n_dw_samples=96):
         # db[k] = alpha * sum dz: the dense-layer oracle on a [N*P*Q, K] matrix with a zero input column
         rows = Nn * P * Q
         _, _, db_ref = oracle.fc_bwd(np.zeros((rows, 1), np.float32), np.zeros((K, 1), np.float32),
-                                     dyin.reshape(rows, K), y=yin.reshape(rows, K), alpha=st.alpha, want_dx=False)
+                                     dyin.reshape(rows, K), alpha=st.alpha, want_dx=False)
         errb = assert_close(e["db"].cpu().numpy(), db_ref, "f32", "conv%d db" % (li + 1))
         say("  conv%d dw (sampled %d) rel err %.2e, db rel err %.2e" % (li + 1, n_dw_samples, err, errb))
         del xin, dyin, yin
