@@ -29,6 +29,8 @@ def _units():
             units.append(("dconv_%s_%s.o" % (pname, "bf16" if bf else "f32"), "dconv_inst.hip",
                           ["-DOWT_INST_PASS=%d" % ps, "-DOWT_INST_BF16=%d" % bf]))
     for bf in (0, 1):
+        units.append(("sconv_%s.o" % ("bf16" if bf else "f32"), "sconv_inst.hip", ["-DOWT_INST_BF16=%d" % bf]))
+    for bf in (0, 1):
         units.append(("sfilter_%s.o" % ("bf16" if bf else "f32"), "sfilter_inst.hip", ["-DOWT_INST_BF16=%d" % bf]))
     for bf in (0, 1):
         units.append(("dfilter_%s.o" % ("bf16" if bf else "f32"), "dfilter_inst.hip", ["-DOWT_INST_BF16=%d" % bf]))

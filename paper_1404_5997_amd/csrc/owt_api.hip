@@ -5,6 +5,7 @@
 #include <vector>
 
 #include "owt_host.hpp"
+#include "sconv.hpp"
 #include "sfilter.hpp"
 
 namespace owt {
@@ -48,7 +49,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -129,8 +130,30 @@ static bool sfilter_geom(const Geom &g, SFilterGeom &sg)
     sg.units_per_image = (g.P + 1) / 2;
     sg.units = g.N * sg.units_per_image;
     const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
-    return sg.NB <= 14 && lds <= 78 * 1024 && g.C <= 16 &&
-           (long)sg.ROWS * (g.W * g.C / 4) <= 256L * kSFilterPNP && (long)sg.DZP * 16 <= 256L * kSFilterDNP;
+    return sg.NB <= 4 * kSFilterACCS && lds <= 150 * 1024 && g.C <= 16 &&
+           (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSFilterNT * kSFilterPNP && (long)sg.DZP * 16 <= (long)kSFilterNT * kSFilterDNP;
+}
+
+// Geometry of the small-channel strided forward kernel; false when it does not apply.
+static bool sconv_geom(const Geom &g, SConvGeom &sg)
+{
+    if ((g.sw * g.C) % 4 || (g.W * g.C) % 4 || g.C > 16 || (g.sh == 1 && g.sw == 1)) return false;
+    sg.SEG = g.S * g.C;
+    sg.LPAD = (4 - (g.pw * g.C) % 4) % 4;
+    sg.SLOTS = (sg.SEG + sg.LPAD + 3) & ~3;
+    const int a = g.pw * g.C + sg.LPAD + g.W * g.C, b = (g.Q - 1) * g.sw * g.C + sg.SLOTS;
+    sg.PITCH = ((a > b ? a : b) + 3) & ~3;
+    sg.ROWS = (kSConvTP - 1) * g.sh + g.R;
+    sg.KSTEPS = (g.R * sg.SLOTS + kSConvBK - 1) / kSConvBK;
+    sg.KSLOTS = sg.KSTEPS * kSConvBK;
+    sg.MPIX = kSConvTP * g.Q;
+    sg.units_per_image = (g.P + kSConvTP - 1) / kSConvTP;
+    sg.units = g.N * sg.units_per_image;
+    // the padded tail of the reduction runs past filter row R-1: those panel rows exist and stay zero
+    const int zr = (kSConvTP - 1) * g.sh + (sg.KSLOTS - 1) / sg.SLOTS + 1;
+    sg.ZROWS = zr > sg.ROWS + 1 ? zr : sg.ROWS + 1;
+    const size_t lds = ((size_t)2 * 64 * (kSConvBK + 4) + (size_t)sg.ZROWS * sg.PITCH) * 4;
+    return sg.MPIX <= 256 && lds <= 150 * 1024 && (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
 }
 
 struct Launch {
@@ -201,6 +224,25 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             }
         }
     }
+    SConvGeom scg;
+    if (pass == OWT_PASS_FWD && !no_direct && sconv_geom(g, scg)) {
+        const long ktiles = cdiv(g.K, 64);
+        for (long target : {256L, 512L}) {
+            long wgs = target / ktiles > 0 ? target / ktiles : 1;
+            if (force_split > 0) wgs = force_split;
+            if (wgs > scg.units) wgs = scg.units;
+            const long per = cdiv(scg.units, wgs), n = cdiv(scg.units, per);
+            Launch l; memset(&l, 0, sizeof(l));
+            l.kind = KIND_SCONV; l.splits = 1; l.steps = scg.units; l.steps_per_split = (int)per;
+            l.tiles_m = (int)ktiles; l.tiles_n = (int)n;
+            l.partial_bytes = pad256((size_t)g.K * scg.KSLOTS * 4);          // the re-laid-out filters
+            l.cost = model_cost(ktiles * n, 8, 1, 256.0 * 64 * scg.KSLOTS * per, 1.0, 1, dm.M, dm.Ncols);
+            bool dup = false;
+            for (const Launch &o : out) dup |= o.kind == l.kind && o.tiles_n == l.tiles_n;
+            if (!dup) out.push_back(l);
+            if (force_split > 0) break;
+        }
+    }
     SFilterGeom sfg;
     if (pass == OWT_PASS_BWD_FILTER && !no_direct && (g.sh > 1 || g.sw > 1) && sfilter_geom(g, sfg)) {
         const long ktiles = cdiv(g.K, 64);
@@ -216,7 +258,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
                 l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                 l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
             }
-            l.cost = model_cost(ktiles * splits, 4, 2, 64.0 * sfg.NB * 32 * sfg.DZP * per, 1.0, splits, dm.M, dm.Ncols);
+            l.cost = model_cost(ktiles * splits, 8, 2, 64.0 * sfg.NB * 32 * sfg.DZP * per, 1.0, splits, dm.M, dm.Ncols);
             bool dup = false;
             for (const Launch &o : out) dup |= o.kind == l.kind && o.splits == l.splits;
             if (!dup) out.push_back(l);
@@ -326,7 +368,14 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
     p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.partial_bytes) : nullptr;
     const bool bf = dt == OWT_BF16;
     hipError_t e;
-    if (l.kind == KIND_SFILTER) {
+    if (l.kind == KIND_SCONV) {
+        SConvGeom sg;
+        sconv_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        p.splits = 1; p.partial = nullptr;
+        e = bf ? owt_launch_sconv_bf16(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s)
+               : owt_launch_sconv_f32(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s);
+    } else if (l.kind == KIND_SFILTER) {
         SFilterGeom sg;
         sfilter_geom(g, sg);
         sg.units_per_wg = l.steps_per_split;
@@ -354,6 +403,9 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
 static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims &dm, const Launch &l)
 {
     static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
+    if (l.kind == KIND_SCONV)
+        return snprintf(buf, n, "sconv %s %s rows%d grid%dx%d", pn[pass], dt == OWT_BF16 ? "bf16" : "f32", kSConvTP,
+                        l.tiles_m, l.tiles_n);
     if (l.kind == KIND_SFILTER)
         return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d", pn[pass], dt == OWT_BF16 ? "bf16" : "f32",
                         l.splits, l.tiles_m, l.splits);
@@ -480,12 +532,14 @@ int owt_selftest_host(void)
             enumerate(g, pass, dm, pass == OWT_PASS_BWD_FILTER, c);
             if (c.empty()) { fail(OWT_EINVAL, "no candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 3; }
             const size_t bound = max_workspace(g, pass, dm, pass == OWT_PASS_BWD_FILTER);
-            for (const Launch &l : c)
-                if (l.splits < 1 || (long)l.splits * l.steps_per_split < l.steps ||
-                    (long)(l.splits - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
+            for (const Launch &l : c) {
+                const long parts = l.kind == KIND_SCONV ? l.tiles_n : l.splits;   // who shares the steps
+                if (l.splits < 1 || parts * l.steps_per_split < l.steps ||
+                    (parts - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
                     (l.kind == KIND_DIRECT && (l.pr > 256 || direct_panel_rows(g, pass, dm) > l.pr))) {
                     fail(OWT_EINVAL, "bad candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 4;
                 }
+            }
         }
     }
     return 0;

@@ -1,0 +1,167 @@
+// Forward pass of a strided convolution with few input channels (the first layer
+// of the Section 5 model: 3 channels, 11x11 filters, stride 4), fp32 MFMA.
+//
+// For a fixed filter row r the S*C inputs of one window are one contiguous run of
+// floats in the NHWC image, so a window row is read as SLOTS = round4(S*C + LPAD)
+// consecutive floats starting LPAD floats left of the window (16-byte aligned for
+// every window because stride_w*C is a multiple of 4); the extra slots meet zero
+// weights.  A work-group keeps the (TP-1)*stride_h + R input rows that TP = 4
+// output rows touch in LDS, zero padding included, and walks the reduction index
+// t = r*SLOTS + jj in steps of 40 slots, streaming the matching slice of the
+// re-laid-out filters w2[k][t] through a double-buffered LDS tile.  Eight
+// wavefronts each own 32 output pixels x 64 filters.  Work-groups loop over
+// (image, 4-row band) units with the next band prefetched into registers.
+#pragma once
+#include "igemm.hpp"
+
+namespace owt {
+
+struct SConvGeom {
+    int SEG, LPAD, SLOTS, PITCH, ROWS, ZROWS, KSLOTS, KSTEPS, units_per_image, units, units_per_wg, MPIX;
+};
+constexpr int kSConvNT = 512, kSConvTP = 4, kSConvBK = 40, kSConvPNP = 8;
+
+// w2[k][t] = w[k][r][jj - LPAD] for t = r*SLOTS + jj inside the filter, else 0 (fp32, K x KSLOTS)
+template <class T>
+__global__ void __launch_bounds__(256) sconv_pack_filters_kernel(const T *__restrict__ w, float *__restrict__ w2,
+                                                                 int K, int R, SConvGeom sg)
+{
+    const int total = K * sg.KSLOTS;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        const int k = i / sg.KSLOTS, t = i - k * sg.KSLOTS;
+        const int r = t / sg.SLOTS, j = t - r * sg.SLOTS - sg.LPAD;
+        w2[i] = (r < R && j >= 0 && j < sg.SEG) ? load1(w, (k * R + r) * sg.SEG + j) : 0.f;
+    }
+}
+
+template <class T>
+__global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams p, const SConvGeom sg, const float *w2)
+{
+    constexpr int NT = kSConvNT, TP = kSConvTP, BK = kSConvBK, WP = BK + 4, KB = 64, PNP = kSConvPNP;
+    constexpr int BQ = BK / 4;                                  // quads per step
+    extern __shared__ __attribute__((aligned(16))) float slds[];
+    float *Bs = slds;                                           // 2 x KB x WP
+    float *panel = slds + 2 * KB * WP;                          // ZROWS x PITCH; rows >= ROWS stay zero
+
+    const Geom &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int li = lane & 31, lh = lane >> 5;
+    const int k0 = blockIdx.x * KB;
+
+    // the pixel this lane feeds to the MFMA: slot m of the band's TP*Q pixels
+    const int m = wave * 32 + li;
+    const int pl = m / g.Q, q = m - pl * g.Q;
+    const bool mvalid = m < sg.MPIX;
+    const int abase = mvalid ? pl * g.sh * sg.PITCH + q * g.sw * g.C : sg.ROWS * sg.PITCH;
+    const int qpr = sg.SLOTS / 4;                               // quads per filter row
+
+    for (int i = tid; i < sg.ZROWS * sg.PITCH; i += NT) panel[i] = 0.f;
+    __syncthreads();
+
+    const T *xsrc = (const T *)p.a;
+    const int row_f4 = g.W * g.C / 4, panel_f4 = sg.ROWS * row_f4;
+    const int img_off = g.pw * g.C + sg.LPAD;
+    float4 preg[PNP], breg[2];
+    const int bq = tid % BQ, bl0 = tid / BQ;                    // filter-slice loader: quad, filter line
+    constexpr int BLPP = NT / BQ;                               // lines per pass (51 for 512 threads)
+
+    auto load_band = [&](int u) {
+        const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
+        const int h0 = p0 * g.sh - g.ph;
+#pragma unroll
+        for (int it = 0; it < PNP; it++) {
+            const int i = tid + it * NT;
+            const int row = i / row_f4, f4 = i - row * row_f4, h = h0 + row;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (i < panel_f4 && (unsigned)h < (unsigned)g.H) v = load4(xsrc, ((n * g.H + h) * g.W) * g.C + f4 * 4);
+            preg[it] = v;
+        }
+    };
+    auto store_band = [&]() {
+#pragma unroll
+        for (int it = 0; it < PNP; it++) {
+            const int i = tid + it * NT;
+            const int row = i / row_f4, f4 = i - row * row_f4;
+            if (i < panel_f4) *(float4 *)(panel + row * sg.PITCH + img_off + f4 * 4) = preg[it];
+        }
+    };
+    auto load_b = [&](int step) {
+#pragma unroll
+        for (int it = 0; it < 2; it++) {
+            const int line = bl0 + it * BLPP, k = k0 + line;
+            breg[it] = (line < KB && k < g.K) ? *(const float4 *)(w2 + (size_t)k * sg.KSLOTS + step * BK + bq * 4)
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+    auto store_b = [&](float *buf) {
+#pragma unroll
+        for (int it = 0; it < 2; it++) {
+            const int line = bl0 + it * BLPP;
+            if (line < KB) *(float4 *)(buf + line * WP + bq * 4) = breg[it];
+        }
+    };
+
+    const int u_beg = blockIdx.y * sg.units_per_wg, u_end = min(sg.units, u_beg + sg.units_per_wg);
+    if (u_beg < u_end) { load_band(u_beg); store_band(); }
+    load_b(0);
+    store_b(Bs);
+    __syncthreads();
+
+    typedef typename EpiFwd<T>::TOut TOut;
+    TOut *out = (TOut *)p.out;
+    int cur = 0;
+    for (int u = u_beg; u < u_end; u++) {
+        const bool more_u = u + 1 < u_end;
+        float16v acc[2];
+#pragma unroll
+        for (int i = 0; i < 2; i++)
+#pragma unroll
+            for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
+        for (int step = 0; step < sg.KSTEPS; step++) {
+            const bool last = step + 1 == sg.KSTEPS;
+            if (!last || more_u) load_b(last ? 0 : step + 1);
+            if (step == 0 && more_u) load_band(u + 1);          // held in registers until the band is done
+            const float *Bc = Bs + cur * KB * WP;
+#pragma unroll
+            for (int cc = 0; cc < BQ / 2; cc++) {
+                const int quad = step * BQ + 2 * cc + lh;
+                const int r = quad / qpr, jq = quad - r * qpr;
+                const float4 a = *(const float4 *)(panel + abase + (mvalid ? r * sg.PITCH + jq * 4 : 0));
+                const float4 b0 = *(const float4 *)(Bc + li * WP + (2 * cc + lh) * 4);
+                const float4 b1 = *(const float4 *)(Bc + (32 + li) * WP + (2 * cc + lh) * 4);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b0.x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b1.x, acc[1], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b0.y, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, b1.y, acc[1], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b0.z, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, b1.z, acc[1], 0, 0, 0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b0.w, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, b1.w, acc[1], 0, 0, 0);
+            }
+            if (!last || more_u) store_b(Bs + (cur ^ 1) * KB * WP);
+            if (last && more_u) {
+                __syncthreads();                                 // every wave is done with this band's rows
+                store_band();
+            }
+            __syncthreads();
+            cur ^= 1;
+        }
+        // ---- epilogue of this band: register r of lane (li, lh) is pixel slot 8*(r/4) + 4*lh + r%4 of
+        // the wavefront's 32, filter li (+32 for the second accumulator)
+        const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
+#pragma unroll
+        for (int r = 0; r < 16; r++) {
+            const int mm = wave * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+            const int ppl = mm / g.Q, qq = mm - ppl * g.Q, pp = p0 + ppl;
+            if (mm >= sg.MPIX || pp >= g.P) continue;
+            const size_t row = ((size_t)n * g.P + pp) * g.Q + qq;
+#pragma unroll
+            for (int i = 0; i < 2; i++) {
+                const int k = k0 + 32 * i + li;
+                if (k < g.K) store1(out, row * g.K + k, EpiFwd<T>::op(p, 0, k, acc[i][r]));
+            }
+        }
+    }
+}
+
+}  // namespace owt

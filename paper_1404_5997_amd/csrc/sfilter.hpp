@@ -11,7 +11,7 @@
 // where a filter row is SLOTS = round4(S*C + LPAD) consecutive floats starting
 // LPAD floats left of the window so that every window start is 16-byte aligned.
 // The 2 x NB accumulator blocks (64 filters x 32-slot blocks) are dealt to the
-// four wavefronts; slots that are padding are simply not stored.  The pixel
+// eight wavefronts of the work-group; slots that are padding are simply not stored.  The pixel
 // range is split over the grid and summed by splitk_reduce_kernel.
 #pragma once
 #include "igemm.hpp"
@@ -22,10 +22,10 @@ struct SFilterGeom {
     int SEG, LPAD, SLOTS, PITCH, ROWS, NB, units_per_image, units, units_per_wg, DZP;
 };
 // float4 staged per thread and unit: input rows (kSFilterPNP) and dz rows (kSFilterDNP)
-constexpr int kSFilterPNP = 10, kSFilterDNP = 7;
+constexpr int kSFilterNT = 512, kSFilterACCS = 4, kSFilterPNP = 5, kSFilterDNP = 4;
 
-template <class T, int ACCS, int PNP, int DNP>
-__global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, const SFilterGeom sg)
+template <class T, int NT, int ACCS, int PNP, int DNP>
+__global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, const SFilterGeom sg)
 {
     constexpr int TP = 2, KB = 64, DZPITCH = KB + 4;
     extern __shared__ __attribute__((aligned(16))) float slds[];
@@ -39,15 +39,15 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
     const int k0 = blockIdx.x * KB;
     const int split = blockIdx.y;
     const int mb = wave & 1;                               // which 32 of the 64 filters this wavefront owns
-    const int nb0 = wave >> 1;                             // its slot blocks: nb0, nb0 + 2, ...
+    const int nb0 = wave >> 1;                             // its slot blocks: nb0, nb0 + NT/128, ...
 
     // per-lane offset of slot t = 32*nb + li inside the panel (relative to the pixel's base)
     int toff[ACCS];
 #pragma unroll
     for (int a = 0; a < ACCS; a++) {
-        const int t = 32 * (nb0 + 2 * a) + li;
+        const int t = 32 * (nb0 + (NT / 128) * a) + li;
         const int r = t / sg.SLOTS, jj = t - r * sg.SLOTS;
-        toff[a] = (nb0 + 2 * a < sg.NB && r < g.R) ? r * sg.PITCH + jj : 0;
+        toff[a] = (nb0 + (NT / 128) * a < sg.NB && r < g.R) ? r * sg.PITCH + jj : 0;
     }
     float16v acc[ACCS];
 #pragma unroll
@@ -56,8 +56,8 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
         for (int r = 0; r < 16; r++) acc[a][r] = 0.f;
 
     // constant parts of LDS: zero padding of the panel rows, pixel -> base table
-    for (int i = tid; i < sg.ROWS * sg.PITCH; i += 256) panel[i] = 0.f;
-    for (int i = tid; i < sg.DZP; i += 256) {
+    for (int i = tid; i < sg.ROWS * sg.PITCH; i += NT) panel[i] = 0.f;
+    for (int i = tid; i < sg.DZP; i += NT) {
         const int pl = i / g.Q, q = i - pl * g.Q;
         pbase[i] = pl < TP ? pl * g.sh * sg.PITCH + q * g.sw * g.C : 0;
     }
@@ -77,7 +77,7 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
         const int h0 = p0 * g.sh - g.ph;
 #pragma unroll
         for (int it = 0; it < PNP; it++) {
-            const int i = tid + it * 256;
+            const int i = tid + it * NT;
             const int row = i / row_f4, f4 = i - row * row_f4, h = h0 + row;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (i < panel_f4 && (unsigned)h < (unsigned)g.H) v = load4(xsrc, ((n * g.H + h) * g.W) * g.C + f4 * 4);
@@ -85,7 +85,7 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
         }
 #pragma unroll
         for (int it = 0; it < DNP; it++) {
-            const int i = tid + it * 256;
+            const int i = tid + it * NT;
             const int pix = i / (KB / 4), kq = i - pix * (KB / 4);
             const int pl = pix / g.Q, q = pix - pl * g.Q, pp = p0 + pl, k = k0 + kq * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -104,13 +104,13 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
     auto store_unit = [&]() {
 #pragma unroll
         for (int it = 0; it < PNP; it++) {
-            const int i = tid + it * 256;
+            const int i = tid + it * NT;
             const int row = i / row_f4, f4 = i - row * row_f4;
             if (i < panel_f4) *(float4 *)(panel + row * sg.PITCH + img_off + f4 * 4) = preg[it];
         }
 #pragma unroll
         for (int it = 0; it < DNP; it++) {
-            const int i = tid + it * 256;
+            const int i = tid + it * NT;
             const int pix = i / (KB / 4), kq = i - pix * (KB / 4);
             if (i < dz_f4) {
                 *(float4 *)(dzs + pix * DZPITCH + kq * 4) = dreg[it];
@@ -125,28 +125,37 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
     for (int u = u_beg; u < u_end; u++) {
         const bool more = u + 1 < u_end;
         if (more) load_unit(u + 1);          // in flight while this unit's MFMAs run
-        // ---- dz^T * windows: two pixels per MFMA, fragments fetched one pair ahead
-        float a_cur = dzs[lh * DZPITCH + mb * 32 + li], b_cur[ACCS];
-        {
-            const int base = pbase[lh];
+        // ---- dz^T * windows: two pixels per MFMA.  Two fragment sets ping-pong so that the LDS
+        // reads of the next pixel pair are issued before the MFMAs of the current one.
+        const int npair = sg.DZP / 2;
+        // fetch(pair, base, ...) reads the fragments of `pair` at the panel offset `base` looked up one
+        // call earlier, and looks up the offset of pair + 2 for the call after next
+        auto fetch = [&](int pair, int &base, float &a, float (&b)[ACCS]) {
+            const int pix = 2 * pair + lh;
+            a = dzs[pix * DZPITCH + mb * 32 + li];
 #pragma unroll
-            for (int a = 0; a < ACCS; a++) b_cur[a] = panel[base + toff[a]];
+            for (int i = 0; i < ACCS; i++) b[i] = panel[base + toff[i]];
+            base = pbase[min(pix + 4, sg.DZP - 1)];
+        };
+        auto mma = [&](float a, const float (&b)[ACCS]) {
+#pragma unroll
+            for (int i = 0; i < ACCS; i++) acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[i], acc[i], 0, 0, 0);
+        };
+        float a0, a1, b0[ACCS], b1[ACCS];
+        int base0 = pbase[lh], base1 = pbase[min(2 + lh, sg.DZP - 1)];
+        fetch(0, base0, a0, b0);
+        int j = 0;
+        for (; j + 1 < npair; j += 2) {
+            fetch(j + 1, base1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(min(j + 2, npair - 1), base0, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll 2
-        for (int j = 0; j < sg.DZP / 2; j++) {
-            float a_nxt, b_nxt[ACCS];
-            const int pix = min(2 * (j + 1) + lh, sg.DZP - 1);
-            const int base = pbase[pix];
-            a_nxt = dzs[pix * DZPITCH + mb * 32 + li];
-#pragma unroll
-            for (int a = 0; a < ACCS; a++) b_nxt[a] = panel[base + toff[a]];
-#pragma unroll
-            for (int a = 0; a < ACCS; a++)
-                acc[a] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b_cur[a], acc[a], 0, 0, 0);
-            a_cur = a_nxt;
-#pragma unroll
-            for (int a = 0; a < ACCS; a++) b_cur[a] = b_nxt[a];
-        }
+        if (j < npair) mma(a0, b0);
         __syncthreads();
         if (more) store_unit();
         __syncthreads();
@@ -158,7 +167,7 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
     float *out = (float *)p.out;
 #pragma unroll
     for (int a = 0; a < ACCS; a++) {
-        const int nb = nb0 + 2 * a, t = 32 * nb + li;
+        const int nb = nb0 + (NT / 128) * a, t = 32 * nb + li;
         const int r = t / sg.SLOTS, j = t - r * sg.SLOTS - sg.LPAD;
         if (nb >= sg.NB || r >= g.R || j < 0 || j >= sg.SEG) continue;
 #pragma unroll
@@ -177,7 +186,7 @@ __global__ void __launch_bounds__(256, 2) sfilter_kernel(const GemmParams p, con
         __syncthreads();
         if (tid < KB && k0 + tid < g.K) {
             float s = 0.f;
-            for (int j = 0; j < 16; j++) s += red[(j * 16 + tid / 4) * 4 + (tid & 3)];
+            for (int j = 0; j < NT / 16; j++) s += red[(j * 16 + tid / 4) * 4 + (tid & 3)];
             const int k = k0 + tid;
             if (part) p.dbias_partial[(size_t)split * p.M + k] = s;
             else p.dbias[k] = p.alpha * s + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);

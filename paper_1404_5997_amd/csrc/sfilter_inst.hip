@@ -22,12 +22,12 @@ hipError_t OWT_FN(const GemmParams &p, const SFilterGeom &sg, int ktiles, hipStr
     const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
     static bool attr_set = false;     // benign race: the attribute is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)sfilter_kernel<TT, 7, kSFilterPNP, kSFilterDNP>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void *)sfilter_kernel<TT, kSFilterNT, kSFilterACCS, kSFilterPNP, kSFilterDNP>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((sfilter_kernel<TT, 7, kSFilterPNP, kSFilterDNP>), dim3(ktiles, p.splits), dim3(256), lds, s, p, sg);
+    hipLaunchKernelGGL((sfilter_kernel<TT, kSFilterNT, kSFilterACCS, kSFilterPNP, kSFilterDNP>), dim3(ktiles, p.splits), dim3(kSFilterNT), lds, s, p, sg);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
     return e;

@@ -149,8 +149,9 @@ def test_every_tile_shape_and_split_k(tile, split, direct):
 @pytest.mark.parametrize("shape,split", [
     ((5, 4, 23, 20, 8, 7, 7, 4, 2), 3), ((2, 3, 24, 24, 72, 7, 7, 4, 3), 0), ((3, 3, 36, 28, 64, 11, 11, 4, 2), 5),
     ((2, 8, 17, 12, 20, 5, 3, (2, 2), (2, 1)), 2), ((2, 3, 224, 224, 64, 11, 11, 4, 2), 0)])
-def test_strided_small_channel_filter_gradient_kernel(shape, split):
-    # first-layer style geometry: the row-panel filter-gradient kernel, forced, with and without a split
+def test_strided_small_channel_kernels(shape, split):
+    # first-layer style geometry: the row-panel forward and filter-gradient kernels, forced, with and
+    # without a forced work-group count
     m = owt()
     N, C, H, W, K, R, S, stride, pad = shape
     os.environ["OWT_ONLY_DIRECT"] = "1"
@@ -159,6 +160,7 @@ def test_strided_small_channel_filter_gradient_kernel(shape, split):
     try:
         d = m.conv_desc(N, C, H, W, K, R, S, stride, pad, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
         assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("sfilter")
+        assert m.owt_conv_plan_describe(d, m.OWT_PASS_FWD).startswith("sconv")
         layer_parity(N, C, H, W, K, R, S, stride, pad, seed=200 + split)
         layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, alpha=0.25, beta=1.0, seed=210 + split)
     finally:
