@@ -22,10 +22,12 @@
 
 namespace owt {
 
-template <class T, class Epi, bool BWD, int WM, int WN, int PR, int BK>
+// MB = 32-row MFMA blocks per wavefront along M (2: 64 x 64 per wavefront; 1: 32 x 64, twice the
+// wavefronts for the same tile, for layers too small to fill the chip otherwise).
+template <class T, class Epi, bool BWD, int WM, int WN, int PR, int BK, int MB>
 __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams p)
 {
-    constexpr int NT = 64 * WM * WN, BM = 64 * WM, BN = 64 * WN, PITCH = BK + 4;
+    constexpr int NT = 64 * WM * WN, BM = 32 * MB * WM, BN = 64 * WN, PITCH = BK + 4;
     constexpr bool BKM = !BWD;                                   // filter slice K-major in forward
     constexpr int BPITCH = BKM ? PITCH : BN + 4;
     constexpr int BT = BKM ? BN * PITCH : BK * BPITCH;           // floats per filter-slice buffer
@@ -42,7 +44,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;
-    const int wm0 = (wave / WN) * 64, wn0 = (wave % WN) * 64;
+    const int wm0 = (wave / WN) * 32 * MB, wn0 = (wave % WN) * 64;
 
     const int ntiles = p.tiles_m * p.tiles_n;
     const int b = blockIdx.x, xcd = b & 7;
@@ -68,9 +70,9 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams
     const int nrows = pin(min(m0 + BM, p.M) - 1, th, tw) + (R - 1) * Wi + S - ps;   // <= PR (host-checked)
 
     // rows this lane feeds to the MFMA
-    int hh[2], ww[2], prow[2];
+    int hh[MB], ww[MB], prow[MB];
 #pragma unroll
-    for (int bm = 0; bm < 2; bm++) {
+    for (int bm = 0; bm < MB; bm++) {
         const int m = m0 + wm0 + bm * 32 + li;
         if (m < p.M) prow[bm] = pin(m, hh[bm], ww[bm]) - ps;
         else { hh[bm] = kInvalidLo; ww[bm] = 0; prow[bm] = 0; }
@@ -127,9 +129,9 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams
             *(float4 *)(buf + (bline0 + i * BRPP) * BPITCH + bquad * 4) = breg[i];
     };
 
-    float16v acc[2][2];
+    float16v acc[MB][2];
 #pragma unroll
-    for (int i = 0; i < 2; i++)
+    for (int i = 0; i < MB; i++)
 #pragma unroll
         for (int j = 0; j < 2; j++)
 #pragma unroll
@@ -154,18 +156,18 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams
             if (more) load_b(last_tap ? ch + 1 : ch, last_tap ? 0 : tap + 1);
             if (tap == 0 && next_chunk) load_panel(ch + 1);      // held in registers until the last tap
 
-            int aoff[2];
+            int aoff[MB];
 #pragma unroll
-            for (int bm = 0; bm < 2; bm++) {
+            for (int bm = 0; bm < MB; bm++) {
                 const bool ok = (unsigned)(hh[bm] + r) < (unsigned)Hi && (unsigned)(ww[bm] + s) < (unsigned)Wi;
                 aoff[bm] = (ok ? prow[bm] + r * Wi + s : PR) * PITCH + lh * 4;
             }
             const float *Bs = lds + cur * BT;
 #pragma unroll
             for (int kc = 0; kc < BK / 8; kc++) {
-                float af[2][4], bf[2][4];
+                float af[MB][4], bf[2][4];
 #pragma unroll
-                for (int bm = 0; bm < 2; bm++) {
+                for (int bm = 0; bm < MB; bm++) {
                     const float4 v = *(const float4 *)(panel + aoff[bm] + kc * 8);
                     af[bm][0] = v.x; af[bm][1] = v.y; af[bm][2] = v.z; af[bm][3] = v.w;
                 }
@@ -185,7 +187,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams
 #pragma unroll
                 for (int jj = 0; jj < 4; jj++)
 #pragma unroll
-                    for (int bm = 0; bm < 2; bm++)
+                    for (int bm = 0; bm < MB; bm++)
 #pragma unroll
                         for (int bn = 0; bn < 2; bn++)
                             acc[bm][bn] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[bm][jj], bf[bn][jj], acc[bm][bn], 0, 0, 0);
@@ -201,7 +203,7 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams
         }
     }
 
-    tile_epilogue<Epi, true, BKM>(p, acc, m0 + wm0, n0 + wn0, li, lh, split);
+    tile_epilogue<Epi, true, BKM, MB>(p, acc, m0 + wm0, n0 + wn0, li, lh, split);
 }
 
 }  // namespace owt

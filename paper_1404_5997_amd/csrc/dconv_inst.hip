@@ -30,11 +30,11 @@ constexpr bool kBwd = true;
 #define OWT_FN OWT_SFX(owt_launch_dconv_data)
 #endif
 
-template <int WM, int WN, int PR, int BK>
+template <int WM, int WN, int PR, int BK, int MB = 2>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    hipLaunchKernelGGL((dconv_kernel<TT, OE, kBwd, WM, WN, PR, BK>), grid, dim3(64 * WM * WN), 0, s, p);
+    hipLaunchKernelGGL((dconv_kernel<TT, OE, kBwd, WM, WN, PR, BK, MB>), grid, dim3(64 * WM * WN), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<OE>(p, s);
     return e;
@@ -50,6 +50,15 @@ hipError_t OWT_FN(int tile, int pr, const GemmParams &p, hipStream_t s)
     } else if (tile == TILE_128x64) {
         if (pr <= 160) return go<2, 1, 160, 16>(p, s);
         if (pr <= 256) return go<2, 1, 256, 16>(p, s);
+    } else if (tile == TILE_128x64H) {
+        if (pr <= 160) return go<4, 1, 160, 32, 1>(p, s);
+        if (pr <= 256) return go<4, 1, 256, 32, 1>(p, s);
+    } else if (tile == TILE_128x128H) {
+        if (pr <= 160) return go<4, 2, 160, 32, 1>(p, s);
+        if (pr <= 256) return go<4, 2, 256, 32, 1>(p, s);
+    } else if (tile == TILE_256x64) {
+        if (pr <= 288) return go<4, 1, 288, 32>(p, s);
+        if (pr <= 384) return go<4, 1, 384, 32>(p, s);
     }
     return hipErrorInvalidValue;
 }

@@ -357,16 +357,17 @@ template <class Acc, int VEC, int ROWS, int BK, int NT> struct TileLoader {
 // Stores one wavefront's 64 x 64 block.  Accumulator register r of lane (li, lh) is
 // row slot 8*(r/4) + 4*lh + r%4, column slot li of its 32 x 32 block; a K-major operand
 // maps block b, slot t to index 32*b + t, an MN-major one to 2*t + b.
-template <class Epi, bool AKM, bool BKM>
-__device__ __forceinline__ void tile_epilogue(const GemmParams &p, const float16v (&acc)[2][2], int row0,
+template <class Epi, bool AKM, bool BKM, int MB = 2>
+__device__ __forceinline__ void tile_epilogue(const GemmParams &p, const float16v (&acc)[MB][2], int row0,
                                               int col0, int li, int lh, int split)
 {
     typedef typename Epi::TOut TOut;
     const bool part = p.splits > 1;
     float *pout = part ? p.partial + (size_t)split * p.M * p.Ncols : nullptr;
     TOut *out = (TOut *)p.out;
+    static_assert(AKM || MB == 2, "an MN-major A operand pairs its two row blocks");
 #pragma unroll
-    for (int bm = 0; bm < 2; bm++) {
+    for (int bm = 0; bm < MB; bm++) {
 #pragma unroll
         for (int r = 0; r < 16; r++) {
             const int rho = 8 * (r / 4) + 4 * lh + (r % 4);

@@ -22,11 +22,14 @@ owt_status fail(owt_status st, const char *fmt, ...)
 }
 void clear_error() { g_err[0] = 0; }
 
-const TileInfo kTiles[NUM_TILES] = {
-    {TILE_128x128, 2, 2, 32, 1.00f},
-    {TILE_128x64, 2, 1, 16, 0.90f},
-    {TILE_64x128, 1, 2, 16, 0.90f},
-    {TILE_64x64, 1, 1, 16, 0.75f},
+const TileInfo kTiles[NUM_TILES + 3] = {
+    {TILE_128x128, 2, 2, 32, 1.00f, 128},
+    {TILE_128x64, 2, 1, 16, 0.90f, 128},
+    {TILE_64x128, 1, 2, 16, 0.90f, 64},
+    {TILE_64x64, 1, 1, 16, 0.75f, 64},
+    {TILE_256x64, 4, 1, 32, 1.00f, 256},
+    {TILE_128x64H, 4, 1, 32, 1.00f, 128},
+    {TILE_128x128H, 4, 2, 32, 1.00f, 128},
 };
 
 static inline long cdiv(long a, long b) { return (a + b - 1) / b; }
@@ -77,8 +80,8 @@ static void dconv_frame(const Geom &g, int pass, GemmParams &p)
     p.dWo.set(p.Wo); p.dHoWo.set(p.Ho * p.Wo);
 }
 
-// LDS panel rows the direct kernel needs for 128-row tiles, or -1 when the pass does not qualify.
-static long direct_panel_rows(const Geom &g, int pass, const PassDims &dm)
+// LDS panel rows the direct kernel needs for BM-row tiles, or -1 when the pass does not qualify.
+static long direct_panel_rows(const Geom &g, int pass, const PassDims &dm, long BM = 128)
 {
     if (pass == OWT_PASS_BWD_FILTER || g.sh != 1 || g.sw != 1 || g.R * g.S == 1) return -1;
     GemmParams f; memset(&f, 0, sizeof(f));
@@ -89,8 +92,8 @@ static long direct_panel_rows(const Geom &g, int pass, const PassDims &dm)
         return n * f.Hi * f.Wi + (rem / f.Wo - f.pah) * f.Wi + (rem % f.Wo - f.paw);
     };
     long need = 0;
-    for (long m0 = 0; m0 < dm.M; m0 += 128) {
-        const long last = (m0 + 128 < dm.M ? m0 + 128 : dm.M) - 1;
+    for (long m0 = 0; m0 < dm.M; m0 += BM) {
+        const long last = (m0 + BM < dm.M ? m0 + BM : dm.M) - 1;
         const long rows = pin(last) - pin(m0) + (g.R - 1) * f.Wi + g.S;
         if (rows > need) need = rows;
     }
@@ -193,7 +196,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         if (force_split > 0) s = force_split < steps ? force_split : steps;
         const long per = cdiv(steps, s), splits = cdiv(steps, per);     // drops empty trailing splits
         const TileInfo &ti = kTiles[tile];
-        const long tm = cdiv(dm.M, 64 * ti.WM), tn = cdiv(dm.Ncols, 64 * ti.WN);
+        const long tm = cdiv(dm.M, ti.BM), tn = cdiv(dm.Ncols, 64 * ti.WN);
         Launch l; memset(&l, 0, sizeof(l));
         l.kind = kind; l.tile = tile; l.pr = pr; l.splits = (int)splits; l.steps = (int)steps;
         l.steps_per_split = (int)per; l.tiles_m = (int)tm; l.tiles_n = (int)tn;
@@ -209,19 +212,20 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
     };
 
     static const long kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256};
-    const long rows = no_direct ? -1 : direct_panel_rows(g, pass, dm);
-    if (rows >= 0 && rows <= 256) {
-        const int pr = rows <= 160 ? 160 : 256;
-        const long cred = pass == OWT_PASS_FWD ? g.C : g.K;
-        for (int t : {TILE_128x128, TILE_128x64}) {
-            if (force_tile >= 0 && force_tile != t) continue;
-            const long bk = t == TILE_128x128 ? 32 : 16, chunks = cdiv(cred, bk);
-            const double macs = 128.0 * 64 * kTiles[t].WN * bk * g.R * g.S;
-            for (long s : kSplits) {
-                if (s > 1 && (chunks / s < 2 || s > 8)) break;
-                add(KIND_DIRECT, t, pr, chunks, s, macs, t == TILE_128x128 ? 2 : 5, t == TILE_128x128 ? 1.25 : 1.1);
-                if (force_split > 0) break;
-            }
+    const long cred = pass == OWT_PASS_FWD ? g.C : g.K;
+    for (int t : {TILE_128x128, TILE_128x64, TILE_256x64, TILE_128x64H, TILE_128x128H}) {
+        if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
+        const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
+        int pr;                                        // panel sizes the kernel is instantiated for
+        if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
+        else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : 256; }
+        const long bk = t == TILE_128x64 ? 16 : 32, chunks = cdiv(cred, bk);
+        const double macs = (double)BM * 64 * kTiles[t].WN * bk * g.R * g.S;
+        for (long s : kSplits) {
+            if (s > 1 && (chunks / s < 2 || s > 8)) break;
+            add(KIND_DIRECT, t, pr, chunks, s, macs, t == TILE_128x64 ? 5 : (t == TILE_128x64H ? 3 : 2),
+                t == TILE_128x64 ? 1.1 : 1.25);
+            if (force_split > 0) break;
         }
     }
     SConvGeom scg;
@@ -305,8 +309,8 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         if (vec && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
         const TileInfo &ti = kTiles[t];
         const long ksteps = cdiv(dm.Kd, ti.BK);
-        const long tiles = cdiv(dm.M, 64 * ti.WM) * cdiv(dm.Ncols, 64 * ti.WN);
-        const double macs = 64.0 * ti.WM * 64 * ti.WN * ti.BK;
+        const long tiles = cdiv(dm.M, ti.BM) * cdiv(dm.Ncols, 64 * ti.WN);
+        const double macs = (double)ti.BM * 64 * ti.WN * ti.BK;
         for (long s : kSplits) {
             if (s > 1 && (ksteps / s < 4 || tiles * s > 4096)) break;
             add(KIND_GATHER, t, 0, ksteps, s, macs, t == TILE_128x128 ? 2 : 5, ti.eff);
@@ -415,11 +419,11 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
                         l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits);
     const TileInfo &ti = kTiles[l.tile];
     if (l.kind == KIND_DIRECT)
-        return snprintf(buf, n, "dconv %s %s tile128x%dx%d panel%d splitk%d grid%dx%d", pn[pass],
-                        dt == OWT_BF16 ? "bf16" : "f32", 64 * ti.WN, l.tile == TILE_128x128 ? 32 : 16, l.pr, l.splits,
+        return snprintf(buf, n, "dconv %s %s tile%dx%dx%d panel%d splitk%d grid%dx%d", pn[pass],
+                        dt == OWT_BF16 ? "bf16" : "f32", ti.BM, 64 * ti.WN, l.tile == TILE_128x64 ? 16 : 32, l.pr, l.splits,
                         l.tiles_m * l.tiles_n, l.splits);
     return snprintf(buf, n, "igemm %s %s tile%dx%dx%d vec%d/%d splitk%d grid%dx%d", pn[pass],
-                    dt == OWT_BF16 ? "bf16" : "f32", 64 * ti.WM, 64 * ti.WN, ti.BK, dm.va ? 4 : 1, dm.vb ? 4 : 1,
+                    dt == OWT_BF16 ? "bf16" : "f32", ti.BM, 64 * ti.WN, ti.BK, dm.va ? 4 : 1, dm.vb ? 4 : 1,
                     l.splits, l.tiles_m * l.tiles_n, l.splits);
 }
 
@@ -536,7 +540,7 @@ int owt_selftest_host(void)
                 const long parts = l.kind == KIND_SCONV ? l.tiles_n : l.splits;   // who shares the steps
                 if (l.splits < 1 || parts * l.steps_per_split < l.steps ||
                     (parts - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
-                    (l.kind == KIND_DIRECT && (l.pr > 256 || direct_panel_rows(g, pass, dm) > l.pr))) {
+                    (l.kind == KIND_DIRECT && (l.pr > 384 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {
                     fail(OWT_EINVAL, "bad candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 4;
                 }
             }

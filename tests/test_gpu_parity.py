@@ -127,7 +127,7 @@ def test_flags_and_scaling_variants():
 
 
 @pytest.mark.parametrize("tile,split,direct", [(0, 1, 0), (1, 1, 0), (2, 1, 0), (3, 1, 0), (0, 3, 0), (1, 4, 0),
-                                               (2, 2, 0), (3, 8, 0), (0, 1, 1), (1, 1, 1), (0, 2, 1), (1, 3, 1), (2, 5, 1)])
+                                               (2, 2, 0), (3, 8, 0), (0, 1, 1), (1, 1, 1), (0, 2, 1), (1, 3, 1), (2, 5, 1), (4, 1, 1), (4, 2, 1), (5, 1, 1), (5, 3, 1), (6, 1, 1), (6, 2, 1)])
 def test_every_tile_shape_and_split_k(tile, split, direct):
     # The planner is overridden so each instantiation of the gather kernel (direct = 0) and of the
     # panel-resident stride-1 kernel (direct = 1), and the two-pass split reduction, are exercised.
