@@ -8,11 +8,13 @@ A step = conv1..5 forward (bias+ReLU fused, 3 max-pools), then 3 pool-backward,
 input is data, so its dx has no consumer).  Inputs live in HBM before the clock
 starts.  Prints ONE JSON line.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper]
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+                  [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper]
 """
 import argparse
 import json
 import os
+import re
 import sys
 import time
 
@@ -20,6 +22,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2516.6}   # MI355X dense MFMA peaks (fp32 matrix, bf16)
+WORKLOADS = {
+    "conv_stack": (3, "config 3: 5-layer conv stack 64/192/384/256/256, fp32, batch 128, 224x224x3, full fwd+bwd"),
+    "conv_stack_fc": (4, "config 4: config-3 stack + FC shard K=8 (512/512/125 columns), fp32, batch 128"),
+    "conv_stack_bf16": (5, "config 5: config-3 stack, bf16 storage / fp32 accumulate, batch 1024"),
+    "conv_stack_paper": (3, "paper filter counts 64/192/384/384/256, fp32, batch 128"),
+}
 
 
 def main():
@@ -27,13 +35,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="conv_stack",
-                    choices=["conv_stack", "conv_stack_fc", "conv_stack_bf16", "conv_stack_paper"])
+    ap.add_argument("--workload", default="conv_stack", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-images", type=int, default=32)
+    ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--per-call-reps", type=int, default=10)
     ap.add_argument("--table", action="store_true", help="also print the per-call table to stderr")
     ap.add_argument("--no-autotune", action="store_true", help="let the cost model pick kernel variants")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="finish with three plain 1 GiB device copies (reference for scaling HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (one worker's share of the method); "
@@ -50,15 +59,13 @@ def main():
     torch.cuda.set_device(0)
     dt = "bf16" if args.workload == "conv_stack_bf16" else "f32"
     N = 1024 if dt == "bf16" else 128
-    cfg = {"conv_stack": 3, "conv_stack_fc": 4, "conv_stack_bf16": 5, "conv_stack_paper": 3}[args.workload]
+    cfg, workload_name = WORKLOADS[args.workload]
     filters = si.PAPER_FILTERS if args.workload == "conv_stack_paper" else None
     layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
     with_fc = args.workload == "conv_stack_fc"
 
-    def rnd(a):
-        if dt != "bf16":
-            return a
-        return torch.from_numpy(a).to(torch.bfloat16).float().numpy()     # input preparation only
+    def rnd(a):   # bf16 workloads: make the seeded inputs bf16-representable (input preparation only)
+        return a if dt != "bf16" else torch.from_numpy(a).to(torch.bfloat16).float().numpy()
 
     st = ConvStack(N, layers, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
                    fc_layers=si.FC_LAYERS if with_fc else None, fc_workers=si.FC_WORKERS)
@@ -106,7 +113,7 @@ def main():
     st.hook = None
     per_call = {tag: float(np.mean([a.elapsed_time(b) for a, b in evs])) for tag, evs in recs.items()}   # ms
 
-    # group convolution launches by the kernel variant the planner picked
+    # group the convolution calls by the kernel variant the library runs for them
     groups = {}
     for li, e in enumerate(st.L):
         Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
@@ -115,16 +122,27 @@ def main():
             tag = "conv%d %s" % (li + 1, pname)
             if tag not in per_call:
                 continue
-            desc = owt.owt_conv_plan_describe(e["desc"], ps).rsplit(" grid", 1)[0]
-            gk = groups.setdefault(desc, dict(ms=0.0, flops=0.0, launches=0, calls=[]))
+            full = owt.owt_conv_plan_describe(e["desc"], ps)
+            variant = full.rsplit(" grid", 1)[0]
+            gk = groups.setdefault(variant, dict(ms=0.0, flops=0.0, launches=0, calls=[], keys=[]))
             gk["ms"] += per_call[tag]; gk["flops"] += fl; gk["launches"] += 1; gk["calls"].append(tag)
+            gk["keys"].append("%s %s %s" % (full.split()[0], pname, re.search(r"threads(\d+)", full).group(1)))
     dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
     achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+
+    # HBM bytes per launch of that variant, from the committed counter summary (profiles/hbm_traffic.json:
+    # FETCH_SIZE / WRITE_SIZE per dispatch, scaled by what a plain copy of known size reads), if it has them
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        table_t = json.load(open(tpath)).get(args.workload, {})
+        got = [table_t[k]["fetch_bytes"] + table_t[k]["write_bytes"] for k in dom["keys"] if k in table_t]
+        if len(got) == len(dom["keys"]):
+            traffic = round(sum(got) / len(got))
     roofline = {"bound": "mfma", "kernel": dom_name, "calls": dom["calls"],
-                "avg_launch_ms": dom["ms"] / dom["launches"],
+                "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
                 "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_TFLOPS[dt], 4), "traffic": None}
-    table = {tag: round(ms, 4) for tag, ms in per_call.items()}
+                "frac": round(achieved / PEAK_TFLOPS[dt], 4), "traffic": traffic}
 
     # ------------------------------------------------------------------ CPU baseline
     cpu = None
@@ -158,20 +176,25 @@ def main():
         "value": round(images_per_s, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
-        "config": {"workload": {"conv_stack": "config 3: 5-layer conv stack 64/192/384/256/256, fp32, batch 128, 224x224x3, full fwd+bwd",
-                                "conv_stack_fc": "config 4: config-3 stack + FC shard K=8 (512/512/125 columns), fp32, batch 128",
-                                "conv_stack_bf16": "config 5: config-3 stack, bf16 storage / fp32 accumulate, batch 1024",
-                                "conv_stack_paper": "paper filter counts 64/192/384/384/256, fp32, batch 128"}[args.workload],
-                   "batch": N, "conv_gflop_per_step": round(conv_flops / 1e9, 2),
+        "config": {"workload": workload_name, "batch": N, "conv_gflop_per_step": round(conv_flops / 1e9, 2),
                    "fc_gflop_per_step": round(fc_flops / 1e9, 2)},
         "tflops": round(tflops, 3), "frac_of_mfma_peak": round(tflops / PEAK_TFLOPS[dt], 4),
-        "roofline": roofline, "cpu_baseline": cpu, "per_call_ms": table,
+        "roofline": roofline, "cpu_baseline": cpu,
+        "per_call_ms": {tag: round(ms, 4) for tag, ms in per_call.items()},
+        "kernel_variants": {k: {"calls": v["calls"], "ms": round(v["ms"], 4),
+                                "tflops": round(v["flops"] / v["ms"] / 1e9, 2)} for k, v in groups.items()},
     }
     if args.table:
         for tag, ms in sorted(per_call.items(), key=lambda kv: -kv[1]):
             print("%-20s %8.3f ms" % (tag, ms), file=sys.stderr)
         for k, v in groups.items():
-            print("%-60s %8.3f ms  %7.2f TFLOP/s" % (k, v["ms"], v["flops"] / v["ms"] / 1e9), file=sys.stderr)
+            print("%-72s %8.3f ms  %7.2f TFLOP/s" % (k, v["ms"], v["flops"] / v["ms"] / 1e9), file=sys.stderr)
+    if args.copy_calibration:
+        a = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB: larger than the 256 MB Infinity Cache
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)
+        torch.cuda.synchronize()
     print(json.dumps(out))
 
 

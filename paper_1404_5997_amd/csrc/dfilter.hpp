@@ -143,32 +143,33 @@ __global__ void __launch_bounds__(64 * WK * WC, 2) dfilter_kernel(const GemmPara
         }
         const bool more = ch + 1 < ch_end;
         if (more) load_chunk(ch + 1);
-        // fragments of pixel pair j+1 are fetched while the MFMAs of pair j run
-        float a_cur, b_cur[TAPS];
-        {
-            const int base = prow_tab[lh] * PB;
-            a_cur = dzs[lh * PA + wk0 + li];
+        // Two fragment sets ping-pong so the LDS reads of the next pixel pair are issued before the
+        // MFMAs of the current one; a pair's panel row is looked up one fetch ahead of its use.
+        auto fetch = [&](int pair, int &prow, float &a, float (&b)[TAPS]) {
+            const int pix = 2 * pair + lh;
+            const int base = prow * PB;
+            a = dzs[pix * PA + wk0 + li];
 #pragma unroll
-            for (int t = 0; t < TAPS; t++) b_cur[t] = panel[base + toff[t]];
-        }
+            for (int t = 0; t < TAPS; t++) b[t] = panel[base + toff[t]];
+            prow = prow_tab[min(pix + 4, BP - 1)];
+        };
+        auto mma = [&](float a, const float (&b)[TAPS]) {
 #pragma unroll
-        for (int j = 0; j < BP / 2; j++) {
-            float a_nxt = 0.f, b_nxt[TAPS];
-            if (j + 1 < BP / 2) {
-                const int pix = 2 * (j + 1) + lh;
-                const int base = prow_tab[pix] * PB;
-                a_nxt = dzs[pix * PA + wk0 + li];
+            for (int t = 0; t < TAPS; t++) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b[t], acc[t], 0, 0, 0);
+        };
+        float a0, a1, b0[TAPS], b1[TAPS];
+        int prow0 = prow_tab[lh], prow1 = prow_tab[2 + lh];
+        fetch(0, prow0, a0, b0);
 #pragma unroll
-                for (int t = 0; t < TAPS; t++) b_nxt[t] = panel[base + toff[t]];
-            }
-#pragma unroll
-            for (int t = 0; t < TAPS; t++)
-                acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(a_cur, b_cur[t], acc[t], 0, 0, 0);
-            if (j + 1 < BP / 2) {
-                a_cur = a_nxt;
-#pragma unroll
-                for (int t = 0; t < TAPS; t++) b_cur[t] = b_nxt[t];
-            }
+        for (int j = 0; j < BP / 2; j += 2) {
+            fetch(j + 1, prow1, a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(min(j + 2, BP / 2 - 1), prow0, a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            mma(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
         }
         __syncthreads();
         if (more) store_chunk();

@@ -406,25 +406,30 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
 
 static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims &dm, const Launch &l)
 {
+    // "... gridAxB threadsT": A x B work-groups, T = total threads of the main kernel's launch (the
+    // figure profilers list as its grid size)
     static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
+    const char *ds = dt == OWT_BF16 ? "bf16" : "f32";
     if (l.kind == KIND_SCONV)
-        return snprintf(buf, n, "sconv %s %s rows%d grid%dx%d", pn[pass], dt == OWT_BF16 ? "bf16" : "f32", kSConvTP,
-                        l.tiles_m, l.tiles_n);
+        return snprintf(buf, n, "sconv %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConvTP, l.tiles_m, l.tiles_n,
+                        (long)l.tiles_m * l.tiles_n * kSConvNT);
     if (l.kind == KIND_SFILTER)
-        return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d", pn[pass], dt == OWT_BF16 ? "bf16" : "f32",
-                        l.splits, l.tiles_m, l.splits);
-    if (l.kind == KIND_DFILTER)
-        return snprintf(buf, n, "dfilter %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d", pn[pass],
-                        dt == OWT_BF16 ? "bf16" : "f32", 32 * kDFilterVariants[l.tile].WK, 32 * kDFilterVariants[l.tile].WC,
-                        l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits);
+        return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d threads%ld", pn[pass], ds, l.splits, l.tiles_m,
+                        l.splits, (long)l.tiles_m * l.splits * kSFilterNT);
+    if (l.kind == KIND_DFILTER) {
+        const DFilterVariant &v = kDFilterVariants[l.tile];
+        return snprintf(buf, n, "dfilter %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds, 32 * v.WK,
+                        32 * v.WC, l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits,
+                        (long)l.tiles_m * l.tiles_n * l.splits * 64 * v.WK * v.WC);
+    }
     const TileInfo &ti = kTiles[l.tile];
+    const long threads = (long)l.tiles_m * l.tiles_n * l.splits * 64 * ti.WM * ti.WN;
     if (l.kind == KIND_DIRECT)
-        return snprintf(buf, n, "dconv %s %s tile%dx%dx%d panel%d splitk%d grid%dx%d", pn[pass],
-                        dt == OWT_BF16 ? "bf16" : "f32", ti.BM, 64 * ti.WN, l.tile == TILE_128x64 ? 16 : 32, l.pr, l.splits,
-                        l.tiles_m * l.tiles_n, l.splits);
-    return snprintf(buf, n, "igemm %s %s tile%dx%dx%d vec%d/%d splitk%d grid%dx%d", pn[pass],
-                    dt == OWT_BF16 ? "bf16" : "f32", ti.BM, 64 * ti.WN, ti.BK, dm.va ? 4 : 1, dm.vb ? 4 : 1,
-                    l.splits, l.tiles_m * l.tiles_n, l.splits);
+        return snprintf(buf, n, "dconv %s %s tile%dx%dx%d waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
+                        ti.BM, 64 * ti.WN, l.tile == TILE_128x64 ? 16 : 32, ti.WM, ti.WN, l.pr, l.splits,
+                        l.tiles_m * l.tiles_n, l.splits, threads);
+    return snprintf(buf, n, "igemm %s %s tile%dx%dx%d vec%d/%d splitk%d grid%dx%d threads%ld", pn[pass], ds, ti.BM,
+                    64 * ti.WN, ti.BK, dm.va ? 4 : 1, dm.vb ? 4 : 1, l.splits, l.tiles_m * l.tiles_n, l.splits, threads);
 }
 
 // ----------------------------------------------------------------- checking
