@@ -28,6 +28,8 @@ def _units():
         for bf in (0, 1):
             units.append(("dconv_%s_%s.o" % (pname, "bf16" if bf else "f32"), "dconv_inst.hip",
                           ["-DOWT_INST_PASS=%d" % ps, "-DOWT_INST_BF16=%d" % bf]))
+    for ps, pname in ((0, "fwd"), (1, "data")):
+        units.append(("dconv16_%s.o" % pname, "dconv_bf16_inst.hip", ["-DOWT_INST_PASS=%d" % ps]))
     for bf in (0, 1):
         units.append(("sconv_%s.o" % ("bf16" if bf else "f32"), "sconv_inst.hip", ["-DOWT_INST_BF16=%d" % bf]))
     for bf in (0, 1):

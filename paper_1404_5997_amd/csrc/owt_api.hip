@@ -38,7 +38,7 @@ static inline size_t pad256(size_t n) { return (n + 255) & ~(size_t)255; }
 bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw)
 {
     g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.R = R; g.S = S;
-    g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw;
+    g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw; g.bf16 = 0;
     g.P = (H + 2 * ph - R) / sh + 1;
     g.Q = (W + 2 * pw - S) / sw + 1;
     if (H + 2 * ph - R < 0 || W + 2 * pw - S < 0) return false;
@@ -52,7 +52,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -162,8 +162,9 @@ static bool sconv_geom(const Geom &g, SConvGeom &sg)
 struct Launch {
     int kind, tile, splits, steps, steps_per_split, tiles_m, tiles_n, pr, taps, groups, ctiles;
     size_t partial_bytes, dbias_bytes;
+    size_t pre_bytes;   // workspace in front of the partials (re-laid-out filters of the bf16 backward-data kernel)
     double cost;   // model estimate, ~clocks
-    size_t ws_bytes() const { return partial_bytes + dbias_bytes; }
+    size_t ws_bytes() const { return pre_bytes + partial_bytes + dbias_bytes; }
 };
 
 // Model: the launch's MACs spread over 256 CUs at the tile's relative efficiency, derated when fewer
@@ -226,6 +227,25 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             add(KIND_DIRECT, t, pr, chunks, s, macs, t == TILE_128x64 ? 5 : (t == TILE_128x64H ? 3 : 2),
                 t == TILE_128x64 ? 1.1 : 1.25);
             if (force_split > 0) break;
+        }
+    }
+    if (g.bf16 && cred % 8 == 0 && !getenv("OWT_NO_BF16_MFMA")) {      // same tiles on the bf16 MFMA, 64-channel chunks
+        for (int t : {TILE_128x128, TILE_128x64, TILE_256x64}) {
+            if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
+            const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
+            int pr;
+            if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
+            else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : 256; }
+            const long chunks = cdiv(cred, 64);
+            const double macs = (double)BM * 64 * kTiles[t].WN * 64 * g.R * g.S / 6.0;   // ~6x the fp32 MFMA rate
+            const size_t n0 = out.size();
+            for (long s : kSplits) {
+                if (s > 1 && (chunks / s < 1 || s > 8 || s > chunks)) break;
+                add(KIND_DIRECT16, t, pr, chunks, s, macs, 2, 1.25);
+                if (force_split > 0) break;
+            }
+            if (pass == OWT_PASS_BWD_DATA)
+                for (size_t i = n0; i < out.size(); i++) out[i].pre_bytes = pad256((size_t)g.K * g.R * g.S * g.C * 2);
         }
     }
     SConvGeom scg;
@@ -303,7 +323,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
     }
     // the gather kernel is the fallback of the stride-1 forward / backward-data kernel, and an
     // alternative worth timing next to the direct filter-gradient kernel
-    const bool have_direct = !out.empty() && out[0].kind == KIND_DIRECT;
+    const bool have_direct = !out.empty() && (out[0].kind == KIND_DIRECT || out[0].kind == KIND_DIRECT16);
     for (int t = 0; t < NUM_TILES && !have_direct; t++) {
         if (!vec && t != TILE_64x64) continue;
         if (vec && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
@@ -330,7 +350,8 @@ static PlanKey plan_key(const Geom &g, int pass, owt_dtype dt)
 
 static bool env_overrides()
 {
-    return getenv("OWT_TILE") || getenv("OWT_SPLITK") || getenv("OWT_NO_DIRECT") || getenv("OWT_ONLY_DIRECT");
+    return getenv("OWT_TILE") || getenv("OWT_SPLITK") || getenv("OWT_NO_DIRECT") || getenv("OWT_ONLY_DIRECT") ||
+           getenv("OWT_NO_BF16_MFMA");
 }
 
 static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, bool want_db, bool use_cache)
@@ -368,11 +389,14 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
     p.g = g; p.M = (int)dm.M; p.Ncols = (int)dm.Ncols; p.Kd = (int)dm.Kd;
     p.splits = l.splits; p.ksteps = l.steps; p.ksteps_per_split = l.steps_per_split;
     p.tiles_m = l.tiles_m; p.tiles_n = l.tiles_n;
-    p.partial = l.splits > 1 ? (float *)ws : nullptr;
-    p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.partial_bytes) : nullptr;
+    p.partial = l.splits > 1 ? (float *)((char *)ws + l.pre_bytes) : nullptr;
+    p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.pre_bytes + l.partial_bytes) : nullptr;
     const bool bf = dt == OWT_BF16;
     hipError_t e;
-    if (l.kind == KIND_SCONV) {
+    if (l.kind == KIND_DIRECT16) {
+        dconv_frame(g, pass, p);
+        e = pass == OWT_PASS_FWD ? owt_launch_dconv16_fwd(l.tile, l.pr, p, s) : owt_launch_dconv16_data(l.tile, l.pr, p, ws, s);
+    } else if (l.kind == KIND_SCONV) {
         SConvGeom sg;
         sconv_geom(g, sg);
         sg.units_per_wg = l.steps_per_split;
@@ -424,6 +448,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     }
     const TileInfo &ti = kTiles[l.tile];
     const long threads = (long)l.tiles_m * l.tiles_n * l.splits * 64 * ti.WM * ti.WN;
+    if (l.kind == KIND_DIRECT16)
+        return snprintf(buf, n, "dconv16 %s %s tile%dx%dx64 waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
+                        ti.BM, 64 * ti.WN, ti.WM, ti.WN, l.pr, l.splits, l.tiles_m * l.tiles_n, l.splits, threads);
     if (l.kind == KIND_DIRECT)
         return snprintf(buf, n, "dconv %s %s tile%dx%dx%d waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
                         ti.BM, 64 * ti.WN, l.tile == TILE_128x64 ? 16 : 32, ti.WM, ti.WN, l.pr, l.splits,
@@ -447,6 +474,7 @@ static owt_status check_conv(const owt_conv_desc *d, Geom &g)
     if (d->flags & ~(unsigned)(OWT_BIAS | OWT_RELU)) return fail(OWT_EINVAL, "unknown flag bits 0x%x", d->flags);
     if (!fill_geom(g, d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w))
         return fail(OWT_EINVAL, "filter larger than the padded input: no output");
+    g.bf16 = d->dtype == OWT_BF16;
     const long xe = (long)d->N * d->H * d->W * d->C, ye = (long)d->N * g.P * g.Q * d->K,
                we = (long)d->K * d->R * d->S * d->C;
     if (xe > kMaxElems || ye > kMaxElems || we > kMaxElems)
@@ -545,7 +573,7 @@ int owt_selftest_host(void)
                 const long parts = l.kind == KIND_SCONV ? l.tiles_n : l.splits;   // who shares the steps
                 if (l.splits < 1 || parts * l.steps_per_split < l.steps ||
                     (parts - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
-                    (l.kind == KIND_DIRECT && (l.pr > 384 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {
+                    ((l.kind == KIND_DIRECT || l.kind == KIND_DIRECT16) && (l.pr > 384 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {
                     fail(OWT_EINVAL, "bad candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 4;
                 }
             }
@@ -679,6 +707,7 @@ static owt_status check_fc(const owt_fc_desc *d, Geom &g, int &o_local)
     if ((long)d->N * d->I > kMaxElems || (long)o_local * d->I > kMaxElems)
         return fail(OWT_EUNSUPPORTED, "tensor with more than 2^31-1 elements");
     fill_geom(g, d->N, d->I, 1, 1, o_local, 1, 1, 1, 1, 0, 0);
+    g.bf16 = d->dtype == OWT_BF16;
     return OWT_OK;
 }
 

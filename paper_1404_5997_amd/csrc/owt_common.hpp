@@ -28,6 +28,7 @@ struct FastDiv {
 // H = W = R = S = 1 case.
 struct Geom {
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
+    int bf16;                 // storage type of the tensors is bf16 (host-side planning only)
     FastDiv dC, dS, dK, dQ, dPQ, dW, dHW, dsh, dsw;
 };
 

@@ -39,6 +39,11 @@ hipError_t owt_launch_dconv_fwd_bf16(int tile, int pr, const GemmParams &, hipSt
 hipError_t owt_launch_dconv_data_f32(int tile, int pr, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dconv_data_bf16(int tile, int pr, const GemmParams &, hipStream_t);
 
+// Panel-resident stride-1 kernel on the bf16 MFMA (dconv_bf16_inst.hip).  The backward-data
+// launcher first writes the flipped, transposed filters to the front of `ws`.
+hipError_t owt_launch_dconv16_fwd(int tile, int pr, const GemmParams &, hipStream_t);
+hipError_t owt_launch_dconv16_data(int tile, int pr, const GemmParams &, void *ws, hipStream_t);
+
 // Direct filter-gradient kernel (dfilter_inst.hip): wavefront grid WK x WC (32 filters x 32
 // channels each), exactly tmax taps per work-group, LDS panel of prf padded-image pixels.
 struct DFilterVariant { int WK, WC, tmax, prf; };

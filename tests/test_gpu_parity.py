@@ -138,11 +138,35 @@ def test_every_tile_shape_and_split_k(tile, split, direct):
         layer_parity(4, 40, 13, 13, 136, 3, 3, 1, 1, seed=60 + tile)     # M = 676, ragged in every tile and chunk
         layer_parity(2, 32, 13, 13, 136, 3, 3, 1, 1, dt="bf16", seed=70 + tile)
         if direct:
+            os.environ["OWT_NO_BF16_MFMA"] = "1"                             # bf16 storage on the fp32 MFMA kernel
+            layer_parity(2, 32, 13, 13, 136, 3, 3, 1, 1, dt="bf16", seed=75 + tile)
+            os.environ.pop("OWT_NO_BF16_MFMA")
             layer_parity(3, 64, 27, 27, 72, 5, 5, 1, 2, seed=80 + tile)      # 240-row panel
             layer_parity(2, 8, 9, 14, 12, 3, 5, 1, (1, 2), seed=84 + tile)   # R != S, H != W
             layer_parity(2, 8, 12, 12, 8, 3, 3, 1, 0, seed=88 + tile)        # pad 0: forward direct, bwd-data gathers
     finally:
-        for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_DIRECT"):
+        for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_DIRECT", "OWT_NO_BF16_MFMA"):
+            os.environ.pop(k, None)
+
+
+@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2)])
+def test_bf16_mfma_direct_kernel(tile, split):
+    # bf16 storage, stride 1, reduction channels a multiple of 8: forward and backward-data run on the
+    # bf16 MFMA kernel (64-channel chunks; backward-data reads re-laid-out filters from the workspace)
+    m = owt()
+    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(tile), str(split)
+    try:
+        for (N, C, H, W, K, R, S, pad), kw in [
+                ((4, 72, 13, 13, 136, 3, 3, 1), {}),                         # ragged last chunk in both passes
+                ((3, 64, 27, 27, 72, 5, 5, 2), {}),                          # 240-row panel
+                ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False)),         # one short chunk, R != S
+                ((2, 192, 13, 13, 200, 3, 3, 1), dict(bias=False))]:         # three / four chunks
+            d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_BF16, m.OWT_BIAS | m.OWT_RELU)
+            for ps in (m.OWT_PASS_FWD, m.OWT_PASS_BWD_DATA):
+                assert m.owt_conv_plan_describe(d, ps).startswith("dconv16"), m.owt_conv_plan_describe(d, ps)
+            layer_parity(N, C, H, W, K, R, S, 1, pad, dt="bf16", seed=300 + 10 * tile + split, **kw)
+    finally:
+        for k in ("OWT_TILE", "OWT_SPLITK"):
             os.environ.pop(k, None)
 
 
