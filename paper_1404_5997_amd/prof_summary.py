@@ -26,6 +26,8 @@ def short(name):
 
 def family(name):
     n = short(name)
+    if n.startswith("dconv_bf16_kernel"):
+        return "dconv16 " + ("fwd" if "EpiFwd" in n else "bwd_data")
     if n.startswith("dconv_kernel"):
         return "dconv " + ("fwd" if "EpiFwd" in n else "bwd_data")
     if n.startswith("dfilter_kernel"):
@@ -120,7 +122,9 @@ def main():
     if traffic:
         tpath = os.path.join(a.out, "hbm_traffic.json")
         allw = json.load(open(tpath)) if os.path.exists(tpath) else {}
-        allw[a.workload] = {k: v for k, v in traffic.items() if "fetch_bytes" in v and "write_bytes" in v}
+        merged = dict(allw.get(a.workload, {}))      # variants seen in earlier profile runs stay listed
+        merged.update({k: v for k, v in traffic.items() if "fetch_bytes" in v and "write_bytes" in v})
+        allw[a.workload] = merged
         allw.setdefault("_calibration", {})[a.workload] = {
             "copy_bytes": COPY_BYTES, "fetch_scale": round(scale.get("fetch", 1.0), 4),
             "write_scale": round(scale.get("write", 1.0), 4),
