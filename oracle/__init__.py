@@ -26,7 +26,7 @@ def build(force=False):
     if force or stale:
         tmp = _LIB_PATH + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O3", "-march=native", "-fopenmp", "-shared", "-fPIC",
-                               "-std=c11", _SRC[0], "-o", tmp])
+                               "-std=c11", _SRC[0], "-o", tmp, "-lm"])
         os.replace(tmp, _LIB_PATH)
     return _LIB_PATH
 
@@ -184,6 +184,38 @@ def maxpool_bwd(dy, argmax, hw, win=3, stride=2):
     getattr(lib(), "oracle_maxpool_bwd_" + sfx)(_p(dy), _p(argmax), _p(dx), *[ctypes.c_int(v) for v in
                                                 (N, H, W, C, win, stride)])
     return dx
+
+
+def sgd_momentum(w, vel, g, mu, eps, omega, gscale=1.0):
+    """Section 5 update rule; returns the new (w, vel), inputs untouched."""
+    sfx, _ = _sfx(w)
+    w2, v2 = np.array(w, dtype=w.dtype, order="C"), np.array(vel, dtype=w.dtype, order="C")
+    g = _c(g, w.dtype)
+    assert w2.shape == v2.shape == g.shape
+    getattr(lib(), "oracle_sgd_momentum_" + sfx)(_p(w2), _p(v2), _p(g), ctypes.c_size_t(w2.size), ctypes.c_double(mu),
+                                                 ctypes.c_double(eps), ctypes.c_double(omega), ctypes.c_double(gscale))
+    return w2, v2
+
+
+def logistic_xent(z, labels, col0=0, scale=1.0):
+    """Independent logistic units + cross-entropy on this shard's columns: (loss[N], dz[N, O])."""
+    sfx, _ = _sfx(z)
+    z = _c(z, z.dtype)
+    labels = np.ascontiguousarray(labels, dtype=np.int32)
+    N, O = z.shape
+    assert labels.shape == (N,)
+    loss, dz = np.empty((N,), dtype=z.dtype), np.empty((N, O), dtype=z.dtype)
+    getattr(lib(), "oracle_logistic_xent_" + sfx)(_p(z), _p(labels), _p(loss), _p(dz), ctypes.c_int(N), ctypes.c_int(O),
+                                                  ctypes.c_int(col0), ctypes.c_double(scale))
+    return loss, dz
+
+
+def scale_hyperparameters(k, eps, omega):
+    """(eps', omega') for a batch k times larger (Section 5)."""
+    e2, o2 = ctypes.c_double(), ctypes.c_double()
+    lib().oracle_scale_hyperparameters(ctypes.c_double(k), ctypes.c_double(eps), ctypes.c_double(omega),
+                                       ctypes.byref(e2), ctypes.byref(o2))
+    return e2.value, o2.value
 
 
 def round_bf16(a):

@@ -7,6 +7,8 @@ The paper states no convolution formula; it relies on the usual definitions
 mathematics of those definitions.
 """
 import itertools
+import math
+import os
 
 import numpy as np
 import pytest
@@ -351,3 +353,112 @@ def test_f32_and_f64_builds_agree():
     y64 = oracle.conv_fwd(x, w, b, 2, 1, True)
     y32 = oracle.conv_fwd(x.astype(np.float32), w.astype(np.float32), b.astype(np.float32), 2, 1, True)
     np.testing.assert_allclose(y32, y64, rtol=1e-5, atol=1e-6)
+
+
+# ------------------------------------------------- update rule (Section 5) ----
+
+def golden():
+    vals = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                vals[line[0]] = float(line[1])
+    return vals
+
+
+def test_weight_decay_example_printed_in_the_paper():
+    # Section 5 prints omega' for batch 128 -> 1024 to 8 significant digits, and its sqrt(k) approximation
+    gv = golden()
+    e2, o2 = oracle.scale_hyperparameters(gv["wd_example_k"], gv["wd_example_eps"], gv["wd_example_omega"])
+    assert abs(e2 - math.sqrt(8.0) * 0.01) < 1e-15
+    assert abs(o2 - gv["wd_example_omega_scaled"]) < 5e-11          # half a unit of the last printed digit
+    assert abs(math.sqrt(gv["wd_example_k"]) * gv["wd_example_omega"] - gv["wd_example_omega_sqrtk"]) < 5e-11
+    assert abs(o2 - gv["wd_example_omega_sqrtk"]) > 1e-8            # the exact form is not the approximation
+
+
+def test_update_rule_weight_decay_closed_form_and_batch_equivalence():
+    # mu = 0, zero gradient: k applications give w0 (1 - eps omega)^k (derivation in Section 5), and one
+    # application with the scaled hyperparameters of a k-times larger batch gives the same weight
+    w0 = rnd(300, 50)
+    eps, omega, k = 0.01, 0.0005, 8
+    w, v = w0.copy(), np.zeros_like(w0)
+    for _ in range(k):
+        w, v = oracle.sgd_momentum(w, v, np.zeros_like(w0), 0.0, eps, omega)
+    np.testing.assert_allclose(w, w0 * (1 - eps * omega) ** k, rtol=1e-14)
+    e2, o2 = oracle.scale_hyperparameters(k, eps, omega)
+    w1, _ = oracle.sgd_momentum(w0, np.zeros_like(w0), np.zeros_like(w0), 0.0, e2, o2)
+    np.testing.assert_allclose(w1, w, rtol=1e-14)
+
+
+def test_update_rule_momentum_geometric_series():
+    # omega = 0, constant gradient g: vel_k = eps g (1 - mu^k)/(1 - mu), w_k = w0 + sum of the velocities;
+    # the gradient enters with a plus sign, as the rule is printed
+    w0, g = rnd(301, 40), rnd(302, 40)
+    mu, eps, k = 0.9, 0.02, 7
+    w, v = w0.copy(), np.zeros_like(w0)
+    for _ in range(k):
+        w, v = oracle.sgd_momentum(w, v, g, mu, eps, 0.0)
+    np.testing.assert_allclose(v, eps * g * (1 - mu ** k) / (1 - mu), rtol=1e-13)
+    tot = sum(eps * g * (1 - mu ** j) / (1 - mu) for j in range(1, k + 1))
+    np.testing.assert_allclose(w, w0 + tot, rtol=1e-13)
+
+
+def test_update_rule_one_step_all_terms():
+    # one step written out with every term non-zero, gscale folding in the batch mean and a descent sign
+    w0, v0, g = rnd(303, 30), rnd(304, 30), rnd(305, 30)
+    mu, eps, omega, gs = 0.9, 0.01, 0.0005, -1.0 / 128
+    w, v = oracle.sgd_momentum(w0, v0, g, mu, eps, omega, gs)
+    dv = 0.9 * v0 + 0.01 * (-g / 128 - 0.0005 * w0)
+    np.testing.assert_allclose(v, dv, rtol=1e-14, atol=1e-18)
+    np.testing.assert_allclose(w, w0 + dv, rtol=1e-14, atol=1e-18)
+    # inputs are not modified, and the float32 build agrees
+    w32, v32 = oracle.sgd_momentum(w0.astype(np.float32), v0.astype(np.float32), g.astype(np.float32), mu, eps, omega, gs)
+    np.testing.assert_allclose(w32, w, rtol=1e-6, atol=1e-7)
+    np.testing.assert_allclose(v32, v, rtol=1e-6, atol=1e-7)
+
+
+# ------------------------------------- logistic output layer (Section 5) ----
+
+def test_logistic_xent_textbook_formula_and_shard_targets():
+    # moderate logits: the plain formulas with s = 1/(1+exp(-z)) written in numpy
+    z = rnd(310, 6, 10) * 3.0
+    labels = np.array([12, 3, 15, 10, 19, 7])          # shard owns classes 10..19: samples 1 and 5 have no target here
+    loss, dz = oracle.logistic_xent(z, labels, col0=10, scale=0.5)
+    t = np.zeros_like(z)
+    for n, l in enumerate(labels):
+        if 10 <= l < 20:
+            t[n, l - 10] = 1.0
+    s = 1.0 / (1.0 + np.exp(-z))
+    np.testing.assert_allclose(loss, -(t * np.log(s) + (1 - t) * np.log(1 - s)).sum(axis=1), rtol=1e-12)
+    np.testing.assert_allclose(dz, 0.5 * (s - t), rtol=1e-12, atol=1e-15)
+    assert t[1].sum() == 0 and t[5].sum() == 0 and t.sum() == 4
+
+
+def test_logistic_xent_gradient_by_finite_differences():
+    z = rnd(311, 4, 7) * 2.0
+    labels = np.array([0, 6, 3, 9])
+    _, dz = oracle.logistic_xent(z, labels, 0, 1.0)
+    h = 1e-6
+    for n in range(4):
+        for j in range(7):
+            zp, zm = z.copy(), z.copy()
+            zp[n, j] += h; zm[n, j] -= h
+            fd = (oracle.logistic_xent(zp, labels)[0].sum() - oracle.logistic_xent(zm, labels)[0].sum()) / (2 * h)
+            assert abs(fd - dz[n, j]) < 1e-8, (n, j, fd, dz[n, j])
+
+
+def test_logistic_xent_extreme_logits_stay_finite():
+    # |z| large: loss -> |z| on the wrong side and -> 0 on the right side, no inf/nan; z = 0 gives log 2 per unit
+    z = np.array([[800.0, -800.0, 0.0, 40.0]])
+    loss, dz = oracle.logistic_xent(z, np.array([1]), 0, 1.0)     # target on the -800 unit
+    assert np.isfinite(loss).all() and np.isfinite(dz).all()
+    np.testing.assert_allclose(loss[0], 800.0 + 800.0 + math.log(2.0) + 40.0, rtol=1e-14)
+    np.testing.assert_allclose(dz[0], [1.0, -1.0, 0.5, 1.0], rtol=0, atol=1e-15)
+    # the shard sums of disjoint column blocks add up to the whole layer's loss
+    zz = rnd(312, 5, 12)
+    lab = np.array([0, 5, 11, 7, 3])
+    whole, _ = oracle.logistic_xent(zz, lab, 0)
+    a, _ = oracle.logistic_xent(zz[:, :7], lab, 0)
+    b, _ = oracle.logistic_xent(zz[:, 7:], lab, 7)
+    np.testing.assert_allclose(a + b, whole, rtol=1e-13)
