@@ -9,7 +9,7 @@ input is data, so its dx has no consumer).  Inputs live in HBM before the clock
 starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
-                  [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper]
+                  [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper|train_step]
 """
 import argparse
 import json
@@ -27,6 +27,8 @@ WORKLOADS = {
     "conv_stack_fc": (4, "config 4: config-3 stack + FC shard K=8 (512/512/125 columns), fp32, batch 128"),
     "conv_stack_bf16": (5, "config 5: config-3 stack, bf16 storage / fp32 accumulate, batch 1024"),
     "conv_stack_paper": (3, "paper filter counts 64/192/384/384/256, fp32, batch 128"),
+    "train_step": (4, "config 4 + logistic output layer + Section 5 weight update: one worker's whole training step, "
+                      "fp32, batch 128"),
 }
 
 
@@ -62,7 +64,8 @@ def main():
     cfg, workload_name = WORKLOADS[args.workload]
     filters = si.PAPER_FILTERS if args.workload == "conv_stack_paper" else None
     layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
-    with_fc = args.workload == "conv_stack_fc"
+    with_fc = args.workload in ("conv_stack_fc", "train_step")
+    train = args.workload == "train_step"
 
     def rnd(a):   # bf16 workloads: make the seeded inputs bf16-representable (input preparation only)
         return a if dt != "bf16" else torch.from_numpy(a).to(torch.bfloat16).float().numpy()
@@ -74,22 +77,31 @@ def main():
     ws = [rnd(w) for w in ws]
     if with_fc:
         fws, fbs = si.fc_params(cfg)
-        st.load(x, ws, bs, fws, fbs, [si.fc_peer_columns(cfg, i, N) for i in range(2)])
+        peers = [si.fc_peer_columns(cfg, i, N) for i in range(2)]
+        st.load(x, ws, bs, fws, fbs, peers)
     else:
         st.load(x, ws, bs)
     g = rnd(si.upstream_grad(cfg, 90, tuple(st.top_grad().shape)))
     st.top_grad().copy_(torch.from_numpy(g).to(st.tdt))
+    if train:     # seeded class labels; momentum 0.9, learning rate 0.01, weight decay 0.0005 (Section 5's example)
+        labels_host = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 95).integers(0, 1000, size=N).astype(np.int32)
+        st.set_labels(labels_host)
+
+    def one_step():
+        st.step()
+        if train:
+            st.update(0.9, 0.01, 0.0005)
     if not args.no_autotune:
         st.autotune()      # set-up, outside the timed region: the library times its variants per layer
     torch.cuda.synchronize()
 
     # ---------------------------------------------------------------- timed region
     for _ in range(args.warmup):
-        st.step()
+        one_step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        st.step()
+        one_step()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -108,7 +120,7 @@ def main():
 
     st.hook = hook
     for _ in range(args.per_call_reps):
-        st.step()
+        one_step()
     torch.cuda.synchronize()
     st.hook = None
     per_call = {tag: float(np.mean([a.elapsed_time(b) for a, b in evs])) for tag, evs in recs.items()}   # ms
@@ -144,6 +156,20 @@ def main():
                 "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_TFLOPS[dt], 4), "traffic": traffic}
 
+    # the HBM-bound kernels of the step: algorithmic bytes (each operand once) over the measured duration
+    esz = 2 if dt == "bf16" else 4
+    hbm = {}
+    for li, e in enumerate(st.L):
+        if e["pool"]:
+            Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+            big, small = Nn * P * Q * K, e["a"].numel()
+            hbm["pool%d fwd" % (li + 1)] = big * esz + small * (esz + 1)             # read y; write pooled + arg-max
+            hbm["pool%d bwd" % (li + 1)] = small * (2 * esz + 1) + big * esz         # read dy, pooled y, arg-max; write dx
+    if train:
+        hbm["sgd update"] = st.n_params * 20                                           # read w, vel, g; write w, vel
+    hbm_kernels = {k: {"bytes": b, "ms": round(per_call[k], 4), "GB/s": round(b / per_call[k] / 1e6, 1),
+                       "frac_of_8TB/s": round(b / per_call[k] / 1e6 / 8000.0, 4)} for k, b in hbm.items() if k in per_call}
+
     # ------------------------------------------------------------------ CPU baseline
     cpu = None
     if not args.no_cpu_baseline:
@@ -159,17 +185,40 @@ def main():
             if L["pool"]:
                 cur, rec["am"] = oracle.maxpool_fwd(y, si.POOL_WIN, si.POOL_STRIDE)
             acts.append(rec)
-        grad = gs if not with_fc else np.zeros_like(cur)
+        what = "conv stack fwd+bwd"
+        if not with_fc:
+            grad = gs
+        else:     # the worker's dense shards (own columns beside the peers' seeded columns), as the GPU step does
+            what = "conv stack + FC shards fwd+bwd" + (" + logistic output + update" if train else "")
+            feats, fin, fout = cur.reshape(n, -1), [], []
+            for i, spec in enumerate(si.FC_LAYERS):
+                if i > 0:
+                    feats = np.concatenate([fout[-1], peers[i - 1][:n]], axis=1)
+                fin.append(feats)
+                fout.append(oracle.fc_fwd(feats, fws[i], fbs[i], spec["relu"]))
+            if train:
+                _, dtop = oracle.logistic_xent(fout[-1], labels_host[:n], 0, 1.0)
+            else:
+                dtop = gs
+            for i in range(len(si.FC_LAYERS) - 1, -1, -1):
+                dxp, dwf, dbf = oracle.fc_bwd(fin[i], fws[i], dtop, y=fout[i] if si.FC_LAYERS[i]["relu"] else None,
+                                              alpha=1.0 / n)
+                if train:
+                    oracle.sgd_momentum(fws[i], np.zeros_like(fws[i]), dwf, 0.9, 0.01, 0.0005, -1.0)
+                dtop = dxp[:, :fout[i - 1].shape[1]] if i > 0 else dxp
+            grad = dtop.reshape(cur.shape)
         for li in range(len(layers) - 1, -1, -1):
             L, rec = layers[li], acts[li]
             if L["pool"]:
                 grad = oracle.maxpool_bwd(grad, rec["am"], rec["y"].shape[1:3], si.POOL_WIN, si.POOL_STRIDE)
-            oracle.conv_bwd_filter(rec["x"], grad, (L["R"], L["R"]), L["stride"], L["pad"], y=rec["y"], alpha=1.0 / n)
+            dwc, dbc = oracle.conv_bwd_filter(rec["x"], grad, (L["R"], L["R"]), L["stride"], L["pad"], y=rec["y"], alpha=1.0 / n)
+            if train:
+                oracle.sgd_momentum(ws[li], np.zeros_like(ws[li]), dwc, 0.9, 0.01, 0.0005, -1.0)
             if li > 0:
                 grad = oracle.conv_bwd_data(grad, ws[li], rec["x"].shape[1:3], L["stride"], L["pad"], y=rec["y"])
         dtc = time.perf_counter() - t0
         cpu = {"value": round(n / dtc, 3), "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "conv stack fwd+bwd (fp32 in, double accumulate) on %d of the %d images, %.1f s" % (n, N, dtc)}
+               "sample": "%s (fp32 in, double accumulate) on %d of the %d images, %.1f s" % (what, n, N, dtc)}
 
     out = {
         "metric": "conv-stack fwd+bwd images/sec at batch 128; TFLOP/s as % MFMA peak",
@@ -180,6 +229,7 @@ def main():
                    "fc_gflop_per_step": round(fc_flops / 1e9, 2)},
         "tflops": round(tflops, 3), "frac_of_mfma_peak": round(tflops / PEAK_TFLOPS[dt], 4),
         "roofline": roofline, "cpu_baseline": cpu,
+        "hbm_kernels": hbm_kernels,
         "per_call_ms": {tag: round(ms, 4) for tag, ms in per_call.items()},
         "kernel_variants": {k: {"calls": v["calls"], "ms": round(v["ms"], 4),
                                 "tflops": round(v["flops"] / v["ms"] / 1e9, 2)} for k, v in groups.items()},

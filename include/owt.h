@@ -180,6 +180,43 @@ owt_status owt_maxpool_bwd_relu(int N, int H, int W, int C, int win, int stride,
                                 const void *dy, const unsigned char *argmax, const void *y_pooled, void *dx,
                                 void *hip_stream);
 
+/* Weight update rule of Section 5, in place, one launch per tensor:
+ *     vel := mu*vel + eps*(gscale*g - omega*w);   w := w + vel
+ * mu = momentum, eps = learning rate, omega = weight decay.  g is the gradient as
+ * the caller holds it (e.g. dw of owt_conv_bwd_filter / owt_fc_shard_bwd);
+ * gscale folds in the batch mean when g is a sum (1/N) and the sign: the rule
+ * as printed ADDS the gradient of an objective that is maximised, a caller that
+ * minimises a loss passes a negative gscale.  w, vel, g: n fp32 values on the
+ * device, 16-byte aligned, w and vel updated in place, g only read.  If
+ * w_bf16_or_null is given it receives the new w rounded to bf16 (nearest even):
+ * the weights a bf16-storage convolution then reads.  n == 0 is a no-op.
+ * Errors: NULL/misaligned pointer or a non-finite coefficient -> OWT_EINVAL. */
+owt_status owt_sgd_momentum_update(size_t n, float *w, float *vel, const float *g, float mu, float eps, float omega,
+                                   float gscale, void *w_bf16_or_null, void *hip_stream);
+
+/* Hyperparameters for a batch k times larger (Section 5, host arithmetic only):
+ * eps_out = sqrt(k)*eps and omega_out = (1 - (1 - eps*omega)^k) / eps_out, so that
+ * one application of weight decay at the new batch size shrinks a weight as much
+ * as k applications did at the old one.  eps_out/omega_out are HOST pointers.
+ * Errors: k or eps not positive and finite, NULL output -> OWT_EINVAL. */
+owt_status owt_scale_hyperparameters(double k, double eps, double omega, double *eps_out, double *omega_out);
+
+/* Output layer of Section 5: independent logistic units trained with
+ * cross-entropy, on the O_local columns [col_offset, col_offset + O_local) of
+ * the layer that this worker owns.  With s = 1/(1+exp(-z)) and target
+ * t[n][j] = 1 if labels[n] == col_offset + j, else 0:
+ *     loss[n]  = - sum_j ( t*log s + (1-t)*log(1-s) )     (this shard's share, fp32)
+ *     dz[n][j] = scale * (s - t)                           (stored in `dtype`)
+ * There is no normalisation across classes, so nothing is needed from the other
+ * workers; the full loss of a sample is the sum of the shards' shares.
+ * z, dz: [N, O_local] in `dtype` (dz may alias z); labels: N ints (class index in
+ * the whole layer; one outside this shard means no positive target here);
+ * loss: N floats.  All device pointers, 16-byte aligned.  Evaluated without
+ * overflow for any finite z.  Errors: non-positive sizes, NULL/misaligned
+ * pointers -> OWT_EINVAL; more than 2^31-1 elements -> OWT_EUNSUPPORTED. */
+owt_status owt_logistic_xent(int N, int O_local, int col_offset, owt_dtype dtype, const void *z, const int *labels,
+                             float scale, float *loss, void *dz, void *hip_stream);
+
 /* Message for the calling thread's most recent non-OK return ("" if none).
  * Points at thread-local static storage; valid until the thread's next call. */
 const char *owt_last_error(void);

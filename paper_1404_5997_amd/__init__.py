@@ -23,7 +23,8 @@ EXPORTS = (
     "owt_conv_workspace_bytes", "owt_fc_workspace_bytes", "owt_conv_fwd", "owt_conv_bwd_data",
     "owt_conv_bwd_filter", "owt_fc_shard_fwd", "owt_fc_shard_bwd", "owt_maxpool_fwd",
     "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe", "owt_conv_autotune",
-    "owt_conv_bwd_data_relu_in", "owt_maxpool_bwd_relu",
+    "owt_conv_bwd_data_relu_in", "owt_maxpool_bwd_relu", "owt_sgd_momentum_update", "owt_scale_hyperparameters",
+    "owt_logistic_xent",
 )
 
 
@@ -65,6 +66,10 @@ _lib.owt_fc_shard_fwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_bwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_maxpool_fwd.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
 _lib.owt_maxpool_bwd.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
+_d = ctypes.c_double
+_lib.owt_sgd_momentum_update.argtypes = [_sz, _vp, _vp, _vp, _f, _f, _f, _f, _vp, _vp]
+_lib.owt_scale_hyperparameters.argtypes = [_d, _d, _d, ctypes.POINTER(_d), ctypes.POINTER(_d)]
+_lib.owt_logistic_xent.argtypes = [_i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp]
 _lib.owt_last_error.restype = ctypes.c_char_p
 _lib.owt_abi_version.restype = _i
 _lib.owt_conv_plan_describe.argtypes = [_cd, _i, ctypes.c_char_p, _sz]
@@ -190,6 +195,22 @@ def owt_maxpool_fwd(N, H, W, C, win, stride, dtype, x, y, argmax, stream=None):
 
 def owt_maxpool_bwd(N, H, W, C, win, stride, dtype, dy, argmax, dx, stream=None):
     _check(_lib.owt_maxpool_bwd(N, H, W, C, win, stride, dtype, _ptr(dy), _ptr(argmax), _ptr(dx), _stream(stream)))
+
+
+def owt_sgd_momentum_update(n, w, vel, g, mu, eps, omega, gscale=1.0, w_bf16=None, stream=None):
+    _check(_lib.owt_sgd_momentum_update(n, _ptr(w), _ptr(vel), _ptr(g), mu, eps, omega, gscale, _ptr(w_bf16),
+                                        _stream(stream)))
+
+
+def owt_scale_hyperparameters(k, eps, omega):
+    e2, o2 = _d(), _d()
+    _check(_lib.owt_scale_hyperparameters(k, eps, omega, ctypes.byref(e2), ctypes.byref(o2)))
+    return e2.value, o2.value
+
+
+def owt_logistic_xent(N, O_local, col_offset, dtype, z, labels, scale, loss, dz, stream=None):
+    _check(_lib.owt_logistic_xent(N, O_local, col_offset, dtype, _ptr(z), _ptr(labels), scale, _ptr(loss), _ptr(dz),
+                                  _stream(stream)))
 
 
 def owt_maxpool_bwd_relu(N, H, W, C, win, stride, dtype, dy, argmax, y_pooled, dx, stream=None):

@@ -19,7 +19,7 @@ FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-u
 
 
 def _units():
-    units = [("owt_api.o", "owt_api.hip", []), ("owt_pool.o", "owt_pool.hip", [])]
+    units = [("owt_api.o", "owt_api.hip", []), ("owt_pool.o", "owt_pool.hip", []), ("owt_update.o", "owt_update.hip", [])]
     for ps, pname in ((0, "fwd"), (1, "data"), (2, "filter")):
         for bf in (0, 1):
             units.append(("igemm_%s_%s.o" % (pname, "bf16" if bf else "f32"), "igemm_inst.hip",

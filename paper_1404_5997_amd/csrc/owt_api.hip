@@ -538,7 +538,7 @@ using namespace owt;
 extern "C" {
 
 const char *owt_last_error(void) { return g_err; }
-int owt_abi_version(void) { return 1; }
+int owt_abi_version(void) { return 2; }
 
 int owt_selftest_host(void)
 {

@@ -14,7 +14,8 @@ import torch
 
 from . import (OWT_BF16, OWT_BIAS, OWT_F32, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER, OWT_PASS_FWD, OWT_RELU,
                conv_desc, fc_desc, owt_conv_autotune, owt_conv_bwd_data, owt_conv_bwd_data_relu_in, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
-               owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_maxpool_bwd_relu, owt_maxpool_fwd)
+               owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_logistic_xent, owt_maxpool_bwd_relu,
+               owt_maxpool_fwd, owt_sgd_momentum_update)
 
 
 class ConvStack:
@@ -37,12 +38,9 @@ class ConvStack:
             d = conv_desc(N, C, H, W, K, R, R, st, pad, self.code, OWT_BIAS | OWT_RELU)
             P, Q = (H + 2 * pad - R) // st + 1, (W + 2 * pad - R) // st + 1
             e = dict(desc=d, desc_bwd=conv_desc(N, C, H, W, K, R, R, st, pad, self.code, OWT_BIAS), geom=(N, C, H, W, K, R, st, pad, P, Q), pool=spec["pool"],
-                     w=torch.empty((K, R, R, C), device=dev, dtype=self.tdt),
-                     b=torch.empty((K,), device=dev, dtype=torch.float32),
+                     wshape=(K, R, R, C), bshape=(K,),
                      y=torch.empty((N, P, Q, K), device=dev, dtype=self.tdt),
-                     dy=torch.empty((N, P, Q, K), device=dev, dtype=self.tdt),
-                     dw=torch.empty((K, R, R, C), device=dev, dtype=torch.float32),
-                     db=torch.empty((K,), device=dev, dtype=torch.float32))
+                     dy=torch.empty((N, P, Q, K), device=dev, dtype=self.tdt))
             for p in (OWT_PASS_FWD, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER):
                 ws_bytes = max(ws_bytes, owt_conv_workspace_bytes(d, p))
             H, W, C = P, Q, K
@@ -66,13 +64,10 @@ class ConvStack:
                 d = fc_desc(N, spec["I"], spec["O_total"], fc_workers, 0, self.code, flags)
                 O = spec["O_total"] // fc_workers
                 f = dict(desc=d, I=spec["I"], O=O, O_total=spec["O_total"], relu=spec["relu"],
-                         w=torch.empty((O, spec["I"]), device=dev, dtype=self.tdt),
-                         b=torch.empty((O,), device=dev, dtype=torch.float32),
+                         wshape=(O, spec["I"]), bshape=(O,),
                          y=torch.empty((N, O), device=dev, dtype=self.tdt),
                          dy=torch.empty((N, O), device=dev, dtype=self.tdt),
-                         dx=torch.empty((N, spec["I"]), device=dev, dtype=self.tdt),
-                         dw=torch.empty((O, spec["I"]), device=dev, dtype=torch.float32),
-                         db=torch.empty((O,), device=dev, dtype=torch.float32))
+                         dx=torch.empty((N, spec["I"]), device=dev, dtype=self.tdt))
                 if i > 0:   # input assembled from own columns + the peers' columns
                     f["x"] = torch.zeros((N, spec["I"]), device=dev, dtype=self.tdt)
                 for p in (OWT_PASS_FWD, OWT_PASS_BWD_DATA):
@@ -81,23 +76,66 @@ class ConvStack:
         if self.F:   # the first dense layer's dx_partial IS the gradient of the last pooled map
             e = self.L[-1]
             self.F[0]["dx"] = (e["da"] if e["pool"] else e["dy"]).view(N, -1)
+        self._carve_parameters(dev)
         self.ws = torch.empty((ws_bytes,), device=dev, dtype=torch.uint8)
+        self.labels = None        # set_labels(): the logistic output layer then produces the top gradient
+        self.loss = torch.zeros((N,), device=dev, dtype=torch.float32)
         self.hook = None
         self.alpha = 1.0 / N      # batch-mean weight gradient (update rule of Section 5)
         self.beta = 0.0
+
+    def _carve_parameters(self, dev):
+        """All weights and biases of the worker live in ONE fp32 array (each tensor padded to a multiple
+        of 8 elements, so every view is 16-byte aligned in fp32 and in bf16), with the gradients and the
+        momentum state in two more arrays of the same layout: the update rule is then one launch over
+        the whole array.  bf16 stacks read a bf16 copy of the weights that the update rewrites."""
+        off, slots = 0, []
+        for e in self.L + self.F:
+            for key, shape in (("w", e["wshape"]), ("b", e["bshape"])):
+                n = 1
+                for v in shape:
+                    n *= v
+                slots.append((e, key, shape, off, n))
+                off += (n + 7) // 8 * 8
+        self.n_params = off
+        self.params = torch.zeros((off,), device=dev, dtype=torch.float32)
+        self.grads = torch.zeros((off,), device=dev, dtype=torch.float32)
+        self.vel = torch.zeros((off,), device=dev, dtype=torch.float32)
+        self.params_bf16 = torch.zeros((off,), device=dev, dtype=torch.bfloat16) if self.dt == "bf16" else None
+        for e, key, shape, o, n in slots:
+            e[key + "32"] = self.params[o:o + n].view(shape)                 # fp32 master
+            e["d" + key] = self.grads[o:o + n].view(shape)
+            if key == "w" and self.dt == "bf16":
+                e["w"] = self.params_bf16[o:o + n].view(shape)
+            else:
+                e[key] = e[key + "32"]
+
+    def update(self, mu, eps, omega, gscale=-1.0):
+        """Weight update rule of Section 5 over every parameter of the worker, one launch.  The
+        gradients in self.grads are batch means of a loss (alpha = 1/N), so the default gscale = -1
+        descends."""
+        self._run("sgd update", owt_sgd_momentum_update, self.n_params, self.params, self.vel, self.grads, mu, eps,
+                  omega, gscale, self.params_bf16)
 
     # ------------------------------------------------------------------ setup
     def load(self, x, ws, bs, fc_ws=None, fc_bs=None, fc_peers=None):
         """Host numpy arrays (already bf16-representable for bf16 stacks) -> device buffers."""
         self.x.copy_(torch.from_numpy(x).to(self.tdt))
         for e, w, b in zip(self.L, ws, bs):
-            e["w"].copy_(torch.from_numpy(w).to(self.tdt)); e["b"].copy_(torch.from_numpy(b))
+            e["w32"].copy_(torch.from_numpy(w)); e["w"].copy_(torch.from_numpy(w).to(self.tdt)); e["b"].copy_(torch.from_numpy(b))
         if self.F:
             for f, w, b in zip(self.F, fc_ws, fc_bs):
-                f["w"].copy_(torch.from_numpy(w).to(self.tdt)); f["b"].copy_(torch.from_numpy(b))
+                f["w32"].copy_(torch.from_numpy(w)); f["w"].copy_(torch.from_numpy(w).to(self.tdt)); f["b"].copy_(torch.from_numpy(b))
             for i, f in enumerate(self.F[1:], start=1):
                 own = self.F[i - 1]["O"]
                 f["x"][:, own:].copy_(torch.from_numpy(fc_peers[i - 1]).to(self.tdt))
+
+    def set_labels(self, labels):
+        """Class index per image (host ints).  From then on backward() starts with the logistic
+        cross-entropy output layer of Section 5 on this worker's columns of the last dense layer
+        (rank 0: columns from 0) instead of a caller-supplied top gradient."""
+        assert self.F, "the output layer sits on the fully-connected shard"
+        self.labels = torch.as_tensor(labels, dtype=torch.int32).to(self.loss.device)
 
     def top_grad(self):
         """Buffer the caller fills with the gradient w.r.t. the stack output."""
@@ -136,6 +174,10 @@ class ConvStack:
         return cur
 
     def backward(self):
+        if self.labels is not None:
+            f = self.F[-1]
+            self._run("fc%d logistic xent" % len(self.F), owt_logistic_xent, self.N, f["O"], 0, self.code, f["y"],
+                      self.labels, 1.0, self.loss, f["dy"])
         for i in range(len(self.F) - 1, -1, -1):
             f = self.F[i]
             self._run("fc%d bwd" % (i + 1), owt_fc_shard_bwd, f["desc"], f["x"], f["w"],

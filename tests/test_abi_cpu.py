@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(m):
 
 def test_host_selftest(m):
     assert m.owt_selftest_host() == 0, m.owt_last_error()
-    assert m.owt_abi_version() == 1
+    assert m.owt_abi_version() == 2
 
 
 def test_bad_descriptors_are_rejected_before_any_launch(m):
@@ -90,3 +90,19 @@ def test_workspace_queries_are_stable_and_sized_for_split_k(m):
     assert a[2] > 0 and a[2] % (384 * 1728 * 4) < 384 * 1728 * 4
     f = m.fc_desc(128, 9216, 4096, 8)
     assert m.owt_fc_workspace_bytes(f, 0) > 0     # 128 x 512 outputs cannot fill 256 CUs without split-K
+
+
+def test_scale_hyperparameters_host_call_matches_the_papers_example(m):
+    # host arithmetic only (no GPU): Section 5's worked example, values as printed in the paper
+    import math
+    vals = {}
+    with open(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "paper_values.txt")) as f:
+        for line in f:
+            line = line.split("#")[0].split()
+            if len(line) == 2:
+                vals[line[0]] = float(line[1])
+    e2, o2 = m.owt_scale_hyperparameters(vals["wd_example_k"], vals["wd_example_eps"], vals["wd_example_omega"])
+    assert abs(e2 - math.sqrt(8.0) * 0.01) < 1e-15
+    assert abs(o2 - vals["wd_example_omega_scaled"]) < 5e-11
+    with pytest.raises(m.OwtError):
+        m.owt_scale_hyperparameters(0.0, 0.01, 0.0005)

@@ -180,3 +180,50 @@ def test_config4_stack_plus_fc_shard_fp32():
     e = st.L[-1]
     pooled_dgrad = to_host(e["da"])           # = fc1's dx_partial, reshaped
     check_conv_stack(st, x, ws, bs, pooled_dgrad, "f32", n_sub=2, n_dw_samples=32)
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_training_step_with_logistic_output_and_weight_update(dt):
+    # One worker's whole step: conv stack + dense shards, logistic cross-entropy output layer on the
+    # worker's 125 columns, backward, and the Section 5 update over every parameter in one launch.
+    # Each added call is checked against the oracle on the GPU's own inputs of that call.
+    N = 128 if dt == "f32" else 64
+    st, x, ws, bs, g, (fws, fbs, peers) = build_stack(4, N, dt, with_fc=True)
+    labels = np.random.default_rng(si.BASE_SEED + 4099).integers(0, 1000, size=N).astype(np.int32)
+    labels[:4] = [0, 124, 125, 999]                      # first / last owned class, two outside the shard
+    st.set_labels(labels)
+    st.step()
+    torch.cuda.synchronize()
+    f = st.F[-1]
+    z = to_host(f["y"])
+    loss_ref, dz_ref = oracle.logistic_xent(z, labels, 0, 1.0)
+    if dt == "bf16":
+        dz_ref = oracle.round_bf16(dz_ref)
+    assert_close(to_host(st.loss), loss_ref, "f32", "loss share")
+    assert_close(to_host(f["dy"]), dz_ref, dt, "dz of the output layer")
+    say("  mean loss share per image %.4f (125 units at logit ~0 -> 125 ln2 = %.4f)" % (loss_ref.mean(), 125 * np.log(2)))
+    # the gradients that the update consumes came out of that backward pass
+    assert np.isfinite(to_host(st.grads)).all() and float(st.grads.abs().max()) > 0
+    p0, v0, g0 = to_host(st.params), to_host(st.vel), to_host(st.grads)
+    mu, eps, omega = 0.9, 0.01, 0.0005
+    for it in range(2):      # second application has non-zero momentum state
+        p_ref, v_ref = oracle.sgd_momentum(p0, v0, g0, mu, eps, omega, -1.0)
+        st.update(mu, eps, omega)
+        torch.cuda.synchronize()
+        p1, v1 = to_host(st.params), to_host(st.vel)
+        assert assert_close(p1, p_ref, "f32", "parameters after update %d" % it) < 1e-6
+        assert assert_close(v1, v_ref, "f32", "momentum after update %d" % it) < 1e-6
+        p0, v0 = p1, v1
+    # views alias the arrays: every layer sees its new weights, bf16 stacks their rounded copy
+    for e in st.L + st.F:
+        w32 = to_host(e["w32"])
+        assert w32.shape == tuple(e["wshape"])
+        if dt == "bf16":
+            np.testing.assert_array_equal(to_host(e["w"]), oracle.round_bf16(w32))
+        else:
+            assert e["w"].data_ptr() == e["w32"].data_ptr()
+    assert not np.array_equal(to_host(st.L[0]["w32"]), ws[0])
+    # and the next step runs on them
+    st.step()
+    torch.cuda.synchronize()
+    assert np.isfinite(to_host(st.loss)).all()
