@@ -537,15 +537,18 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) igemm_kernel(const GemmParams
 
 // Sum the split-K partials and apply the epilogue: out[i] = op(sum_s partial[s][i]).
 // The sum over splits always runs in the same order, so results are bit-identical run to run.
-// SG == 1: one thread per element (few splits, many elements).  SG == 8: eight threads per
-// element, each summing every eighth split, combined through LDS in a fixed order (many splits
-// of a small result, e.g. a filter gradient reduced over hundreds of work-groups).
+// Four consecutive results per thread (16-byte loads of every partial), SG threads per group of
+// four, each summing every SG-th split with several loads in flight and combined through LDS in a
+// fixed order: SG = 1 for few splits of a big result, 4 / 16 for the many splits of a small one
+// (a filter gradient reduced over hundreds of work-groups).  The bias-gradient partials are summed
+// by one work-group per filter.  Needs M*N to be a multiple of 4; SG == 0 is the scalar kernel for
+// the other shapes.
 template <class Epi, int SG>
 __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p)
 {
     typedef typename Epi::TOut TOut;
     const size_t total = (size_t)p.M * p.Ncols;
-    if (SG == 1) {
+    if constexpr (SG == 0) {
         for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
             float s = 0.f;
             for (int sp = 0; sp < p.splits; sp++) s += p.partial[(size_t)sp * total + i];
@@ -553,31 +556,56 @@ __global__ void __launch_bounds__(256) splitk_reduce_kernel(const GemmParams p)
             store1((TOut *)p.out, i, Epi::op(p, row, col, s));
         }
     } else {
-        __shared__ float red[SG][256 / SG];
-        constexpr int EPB = 256 / SG;                      // elements per block
+        constexpr int EPB = 256 / SG;                          // groups of four results per block
+        __shared__ float4 red[SG][EPB];
+        const size_t nvec = total >> 2;
         const int e = threadIdx.x % EPB, sg = threadIdx.x / EPB;
-        for (size_t i0 = (size_t)blockIdx.x * EPB; i0 < total; i0 += (size_t)gridDim.x * EPB) {
-            const size_t i = i0 + e;
-            float s = 0.f;
-            if (i < total)
-                for (int sp = sg; sp < p.splits; sp += SG) s += p.partial[(size_t)sp * total + i];
-            red[sg][e] = s;
-            __syncthreads();
-            if (sg == 0 && i < total) {
-                float t = 0.f;
-#pragma unroll
-                for (int j = 0; j < SG; j++) t += red[j][e];
-                const int row = (int)(i / p.Ncols), col = (int)(i - (size_t)row * p.Ncols);
-                store1((TOut *)p.out, i, Epi::op(p, row, col, t));
+        for (size_t v0 = (size_t)blockIdx.x * EPB; v0 < nvec; v0 += (size_t)gridDim.x * EPB) {
+            const size_t v = v0 + e;
+            float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (v < nvec) {
+#pragma unroll 4
+                for (int sp = sg; sp < p.splits; sp += SG) {
+                    const float4 t = *(const float4 *)(p.partial + (size_t)sp * total + 4 * v);
+                    s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w;
+                }
             }
-            __syncthreads();
+            if (SG > 1) {
+                red[sg][e] = s;
+                __syncthreads();
+                if (sg == 0) {
+                    s = red[0][e];
+#pragma unroll
+                    for (int j = 1; j < SG; j++) { const float4 t = red[j][e]; s.x += t.x; s.y += t.y; s.z += t.z; s.w += t.w; }
+                }
+            }
+            if (sg == 0 && v < nvec) {
+                const float r[4] = {s.x, s.y, s.z, s.w};
+                const size_t i = 4 * v;
+                int row = (int)(i / p.Ncols), col = (int)(i - (size_t)row * p.Ncols);
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    store1((TOut *)p.out, i + j, Epi::op(p, row, col, r[j]));
+                    if (++col == p.Ncols) { col = 0; row++; }
+                }
+            }
+            if (SG > 1) __syncthreads();
         }
     }
     if (Epi::DBIAS && p.dbias) {
-        for (int k = blockIdx.x * 256 + threadIdx.x; k < p.M; k += gridDim.x * 256) {
+        __shared__ float rb[256];
+        for (int k = blockIdx.x; k < p.M; k += gridDim.x) {
             float s = 0.f;
-            for (int sp = 0; sp < p.splits; sp++) s += p.dbias_partial[(size_t)sp * p.M + k];
-            p.dbias[k] = p.alpha * s + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);
+            for (int sp = threadIdx.x; sp < p.splits; sp += 256) s += p.dbias_partial[(size_t)sp * p.M + k];
+            rb[threadIdx.x] = s;
+            __syncthreads();
+#pragma unroll
+            for (int d = 128; d >= 1; d >>= 1) {
+                if ((int)threadIdx.x < d) rb[threadIdx.x] += rb[threadIdx.x + d];
+                __syncthreads();
+            }
+            if (threadIdx.x == 0) p.dbias[k] = p.alpha * rb[0] + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);
+            __syncthreads();
         }
     }
 }
@@ -586,15 +614,17 @@ template <class Epi>
 static inline hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s)
 {
     const size_t total = (size_t)p.M * p.Ncols;
-    if (p.splits >= 16) {
-        size_t blocks = (total + 31) / 32;
-        if (blocks > 65536) blocks = 65536;
-        hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 8>), dim3((unsigned)blocks), dim3(256), 0, s, p);
-    } else {
+    if (total % 4 != 0) {
         size_t blocks = (total + 255) / 256;
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 1>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+        hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 0>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+        return hipGetLastError();
     }
+    const size_t nvec = total / 4;
+    auto blocks_for = [&](int epb) { const size_t b = (nvec + epb - 1) / epb; return (unsigned)(b > 16384 ? 16384 : b); };
+    if (p.splits <= 6) hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 1>), dim3(blocks_for(256)), dim3(256), 0, s, p);
+    else if (p.splits <= 32) hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 4>), dim3(blocks_for(64)), dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<Epi, 16>), dim3(blocks_for(16)), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -78,6 +78,7 @@ class ConvStack:
             self.F[0]["dx"] = (e["da"] if e["pool"] else e["dy"]).view(N, -1)
         self._carve_parameters(dev)
         self.ws = torch.empty((ws_bytes,), device=dev, dtype=torch.uint8)
+        self.graph = None
         self.labels = None        # set_labels(): the logistic output layer then produces the top gradient
         self.loss = torch.zeros((N,), device=dev, dtype=torch.float32)
         self.hook = None
@@ -210,6 +211,22 @@ class ConvStack:
     def step(self):
         self.forward()
         self.backward()
+
+    def capture(self):
+        """Record one step into a HIP graph; replay() then runs it with a single launch from the host
+        (worth it when the step is launch-bound, i.e. small batches; at batch 128 the kernels are long
+        enough that replay and eager launches take the same time).  The graph reads and writes this
+        object's buffers."""
+        assert self.hook is None
+        self.step()                                   # nothing inside the capture runs for the first time
+        torch.cuda.synchronize()
+        self.graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.graph):
+            self.step()
+        return self.graph
+
+    def replay(self):
+        self.graph.replay()
 
     def autotune(self):
         """Let the library time its kernel variants for every convolution pass of the stack on the

@@ -227,3 +227,21 @@ def test_training_step_with_logistic_output_and_weight_update(dt):
     st.step()
     torch.cuda.synchronize()
     assert np.isfinite(to_host(st.loss)).all()
+
+
+def test_hip_graph_replay_of_a_step_equals_eager_launches():
+    # the step recorded into a HIP graph (no memset nodes: the library records kernels only) and replayed
+    # several times, with eager steps and synchronisations in between, gives the eager step's bits
+    st, x, ws, bs, g, _ = build_stack(4, 8, "f32", with_fc=True)
+    st.step()
+    torch.cuda.synchronize()
+    ref_g, ref_y, ref_dx = st.grads.clone(), st.F[-1]["y"].clone(), st.L[1]["dy"].clone()
+    st.capture()
+    for it in range(4):
+        st.grads.zero_(); st.F[-1]["y"].zero_(); st.L[1]["dy"].zero_()
+        st.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(st.grads, ref_g) and torch.equal(st.F[-1]["y"], ref_y) and torch.equal(st.L[1]["dy"], ref_dx), it
+        st.step()                                   # eager work between replays
+        torch.cuda.synchronize()
+        assert torch.equal(st.grads, ref_g)
