@@ -24,8 +24,9 @@ namespace owt {
 
 // MB = 32-row MFMA blocks per wavefront along M (2: 64 x 64 per wavefront; 1: 32 x 64, twice the
 // wavefronts for the same tile, for layers too small to fill the chip otherwise).
-template <class T, class Epi, bool BWD, int WM, int WN, int PR, int BK, int MB>
-__global__ void __launch_bounds__(64 * WM * WN, 2) dconv_kernel(const GemmParams p)
+// OCC = work-groups the register budget is cut for per CU (waves per SIMD when a work-group has four).
+template <class T, class Epi, bool BWD, int WM, int WN, int PR, int BK, int MB, int OCC = 2>
+__global__ void __launch_bounds__(64 * WM * WN, OCC) dconv_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WM * WN, BM = 32 * MB * WM, BN = 64 * WN, PITCH = BK + 4;
     constexpr bool BKM = !BWD;                                   // filter slice K-major in forward

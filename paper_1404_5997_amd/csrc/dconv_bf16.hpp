@@ -19,17 +19,6 @@ namespace owt {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
-// wt[(c*RS + t)*K + k] = w[(k*RS + RS-1-t)*C + c]
-static __global__ void __launch_bounds__(256) flip_transpose_filters_kernel(const uint16_t *__restrict__ w,
-                                                                     uint16_t *__restrict__ wt, int K, int RS, int C)
-{
-    const int total = K * RS * C;
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
-        const int k = i % K, ct = i / K, t = ct % RS, c = ct / RS;
-        wt[i] = w[(k * RS + (RS - 1 - t)) * C + c];
-    }
-}
-
 // zero the bf16 lanes of v whose mask value (bf16 bits in y) is not > 0
 __device__ __forceinline__ uint32_t mask_pair(uint32_t v, uint32_t y)
 {

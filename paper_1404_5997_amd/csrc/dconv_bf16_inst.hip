@@ -49,7 +49,7 @@ hipError_t owt_launch_dconv16_data(int tile, int pr, const GemmParams &p0, void 
 {
     const Geom &g = p0.g;
     const int total = g.K * g.R * g.S * g.C;
-    hipLaunchKernelGGL(flip_transpose_filters_kernel, dim3((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256), dim3(256),
+    hipLaunchKernelGGL(flip_transpose_filters_kernel<uint16_t>, dim3((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256), dim3(256),
                        0, s, (const uint16_t *)p0.b, (uint16_t *)ws, g.K, g.R * g.S, g.C);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -30,11 +30,11 @@ constexpr bool kBwd = true;
 #define OWT_FN OWT_SFX(owt_launch_dconv_data)
 #endif
 
-template <int WM, int WN, int PR, int BK, int MB = 2>
+template <int WM, int WN, int PR, int BK, int MB = 2, int OCC = 2>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    hipLaunchKernelGGL((dconv_kernel<TT, OE, kBwd, WM, WN, PR, BK, MB>), grid, dim3(64 * WM * WN), 0, s, p);
+    hipLaunchKernelGGL((dconv_kernel<TT, OE, kBwd, WM, WN, PR, BK, MB, OCC>), grid, dim3(64 * WM * WN), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<OE>(p, s);
     return e;
@@ -51,7 +51,8 @@ hipError_t OWT_FN(int tile, int pr, const GemmParams &p, hipStream_t s)
         if (pr <= 160) return go<2, 1, 160, 16>(p, s);
         if (pr <= 256) return go<2, 1, 256, 16>(p, s);
     } else if (tile == TILE_128x64H) {
-        if (pr <= 160) return go<4, 1, 160, 32, 1>(p, s);
+        if (pr <= 160) return go<4, 1, 160, 32, 1, 3>(p, s);     // 42 KB of LDS, 126 registers: three per CU
+        if (pr <= 244) return go<4, 1, 244, 32, 1, 3>(p, s);     // 53 KB of LDS: three work-groups per CU
         if (pr <= 256) return go<4, 1, 256, 32, 1>(p, s);
     } else if (tile == TILE_128x128H) {
         if (pr <= 160) return go<4, 2, 160, 32, 1>(p, s);

@@ -628,4 +628,17 @@ static inline hipError_t launch_splitk_reduce(const GemmParams &p, hipStream_t s
     return hipGetLastError();
 }
 
+// Filters re-laid-out for a backward-data pass that wants them contiguous along its reduction
+// index k, with the taps flipped:  wt[(c*RS + t)*K + k] = w[(k*RS + RS-1-t)*C + c]
+template <class T>
+__global__ void __launch_bounds__(256) flip_transpose_filters_kernel(const T *__restrict__ w, T *__restrict__ wt, int K,
+                                                                     int RS, int C)
+{
+    const int total = K * RS * C;
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < total; i += gridDim.x * 256) {
+        const int k = i % K, ct = i / K, t = ct % RS, c = ct / RS;
+        wt[i] = w[(k * RS + (RS - 1 - t)) * C + c];
+    }
+}
+
 }  // namespace owt

@@ -219,7 +219,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
         int pr;                                        // panel sizes the kernel is instantiated for
         if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
-        else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : 256; }
+        else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : ((t == TILE_128x64H && rows <= 244) ? 244 : 256); }
         const long bk = t == TILE_128x64 ? 16 : 32, chunks = cdiv(cred, bk);
         const double macs = (double)BM * 64 * kTiles[t].WN * bk * g.R * g.S;
         for (long s : kSplits) {
