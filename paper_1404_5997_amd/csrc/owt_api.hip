@@ -1,4 +1,5 @@
 // C ABI entry points of libowt: descriptor checks, launch planning, tuning, launches.
+#include <algorithm>
 #include <array>
 #include <map>
 #include <mutex>
@@ -213,6 +214,16 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
     };
 
     static const long kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256};
+    // split counts to try for `tiles` output tiles: the fixed ladder plus the counts that fill one, two
+    // or three rounds of the chip's work-group slots exactly (256 CUs x 2 resident work-groups)
+    auto split_ladder = [&](long tiles) {
+        std::vector<long> v(kSplits, kSplits + sizeof(kSplits) / sizeof(kSplits[0]));
+        for (long rounds = 1; rounds <= 3; rounds++)
+            if (512 * rounds / tiles >= 1) v.push_back(512 * rounds / tiles);
+        std::sort(v.begin(), v.end());
+        v.erase(std::unique(v.begin(), v.end()), v.end());
+        return v;
+    };
     const long cred = pass == OWT_PASS_FWD ? g.C : g.K;
     for (int t : {TILE_128x128, TILE_128x64, TILE_256x64, TILE_128x64H, TILE_128x128H}) {
         if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
@@ -298,7 +309,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             const DFilterVariant &dv = kDFilterVariants[v];
             const long KT = 32 * dv.WK, CT = 32 * dv.WC;
             const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, 32);
-            for (long s0 : kSplits) {
+            for (long s0 : split_ladder(tm * ctl * groups)) {
                 long s = s0;
                 if (force_split > 0) s = force_split < steps ? force_split : steps;
                 else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 2560)) break;
@@ -331,7 +342,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         const long ksteps = cdiv(dm.Kd, ti.BK);
         const long tiles = cdiv(dm.M, ti.BM) * cdiv(dm.Ncols, 64 * ti.WN);
         const double macs = (double)ti.BM * 64 * ti.WN * ti.BK;
-        for (long s : kSplits) {
+        for (long s : split_ladder(tiles)) {
             if (s > 1 && (ksteps / s < 4 || tiles * s > 4096)) break;
             add(KIND_GATHER, t, 0, ksteps, s, macs, t == TILE_128x128 ? 2 : 5, ti.eff);
             if (force_split > 0) break;
