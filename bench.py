@@ -9,7 +9,8 @@ input is data, so its dx has no consumer).  Inputs live in HBM before the clock
 starts.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
-                  [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper|train_step]
+                  [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper|train_step|
+                              train_step_kpass]
 """
 import argparse
 import json
@@ -29,6 +30,8 @@ WORKLOADS = {
     "conv_stack_paper": (3, "paper filter counts 64/192/384/384/256, fp32, batch 128"),
     "train_step": (4, "config 4 + logistic output layer + Section 5 weight update: one worker's whole training step, "
                       "fp32, batch 128"),
+    "train_step_kpass": (4, "train_step under scheme (b) of Section 4 with K = 8: conv stack on the own 128 images, eight "
+                            "fwd+bwd iterations of the FC shards (own batch + 7 seeded peer batches), update; fp32"),
 }
 
 
@@ -43,6 +46,8 @@ def main():
     ap.add_argument("--per-call-reps", type=int, default=10)
     ap.add_argument("--table", action="store_true", help="also print the per-call table to stderr")
     ap.add_argument("--no-autotune", action="store_true", help="let the cost model pick kernel variants")
+    ap.add_argument("--kpass-overlap", action="store_true",
+                    help="train_step_kpass: run the FC iterations on the peers' batches on a second stream")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="finish with three plain 1 GiB device copies (reference for scaling HBM counters)")
     args = ap.parse_args()
@@ -64,8 +69,9 @@ def main():
     cfg, workload_name = WORKLOADS[args.workload]
     filters = si.PAPER_FILTERS if args.workload == "conv_stack_paper" else None
     layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
-    with_fc = args.workload in ("conv_stack_fc", "train_step")
-    train = args.workload == "train_step"
+    kpass = args.workload == "train_step_kpass"
+    with_fc = args.workload in ("conv_stack_fc", "train_step", "train_step_kpass")
+    train = args.workload in ("train_step", "train_step_kpass")
 
     def rnd(a):   # bf16 workloads: make the seeded inputs bf16-representable (input preparation only)
         return a if dt != "bf16" else torch.from_numpy(a).to(torch.bfloat16).float().numpy()
@@ -87,7 +93,18 @@ def main():
         labels_host = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 95).integers(0, 1000, size=N).astype(np.int32)
         st.set_labels(labels_host)
 
-    def one_step():
+    KW = si.FC_WORKERS
+    if kpass:     # what the other K-1 workers would broadcast: seeded activations of the last-stage shape, and labels
+        gk = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 96)
+        peer_feats = [torch.from_numpy(np.maximum(gk.standard_normal((N, st.F[0]["I"]), dtype=np.float32), 0) * np.float32(0.05)).cuda()
+                      for _ in range(KW - 1)]
+        klabels = [torch.from_numpy(gk.integers(0, 1000, size=N).astype(np.int32)).cuda() for _ in range(KW)]
+
+    def one_step(per_pass=None, overlap=args.kpass_overlap):
+        if kpass:
+            st.step_kpass(peer_feats, klabels, per_pass, overlap)
+            st.update(0.9, 0.01, 0.0005, part="conv" if per_pass else "all")
+            return
         st.step()
         if train:
             st.update(0.9, 0.01, 0.0005)
@@ -107,7 +124,11 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     images_per_s = N / (ms_per_step * 1e-3)
     conv_flops, fc_flops = st.conv_flops(), st.fc_flops()
-    tflops = (conv_flops + fc_flops) / (ms_per_step * 1e-3) / 1e12
+    if kpass:
+        fc_total = fc_flops * si.FC_WORKERS
+    else:
+        fc_total = fc_flops
+    tflops = (conv_flops + fc_total) / (ms_per_step * 1e-3) / 1e12
 
     # ------------------------------------------------- per-call durations (HIP events)
     # Events are recorded on torch's current stream, which is the stream the binding launches on.
@@ -119,10 +140,30 @@ def main():
         recs.setdefault(tag, []).append((a, b))
 
     st.hook = hook
-    for _ in range(args.per_call_reps):
-        one_step()
+    for _ in range(args.per_call_reps):    # (the K-pass workload is broken down as one plain step + update)
+        st.step()
+        if train:
+            st.update(0.9, 0.01, 0.0005)
     torch.cuda.synchronize()
     st.hook = None
+
+    schedule = None
+    if kpass:    # the four ways to run the K iterations, same work each: ms per step
+        def timed(**kw):
+            for _ in range(3):
+                one_step(**kw)
+            torch.cuda.synchronize()
+            ta = time.perf_counter()
+            for _ in range(args.steps):
+                one_step(**kw)
+            torch.cuda.synchronize()
+            return round((time.perf_counter() - ta) * 1e3 / args.steps, 4)
+        upd = (0.9, 0.01, 0.0005)
+        schedule = {"K": KW, "fc_gflop_per_step": round(fc_flops * KW / 1e9, 2),
+                    "accumulate_serial_ms": timed(per_pass=None, overlap=False),
+                    "accumulate_overlap_ms": timed(per_pass=None, overlap=True),
+                    "update_every_pass_serial_ms": timed(per_pass=upd, overlap=False),
+                    "update_every_pass_overlap_ms": timed(per_pass=upd, overlap=True)}
     per_call = {tag: float(np.mean([a.elapsed_time(b) for a, b in evs])) for tag, evs in recs.items()}   # ms
 
     # group the convolution calls by the kernel variant the library runs for them
@@ -166,7 +207,7 @@ def main():
             hbm["pool%d fwd" % (li + 1)] = big * esz + small * (esz + 1)             # read y; write pooled + arg-max
             hbm["pool%d bwd" % (li + 1)] = small * (2 * esz + 1) + big * esz         # read dy, pooled y, arg-max; write dx
     if train:
-        hbm["sgd update"] = st.n_params * 20                                           # read w, vel, g; write w, vel
+        hbm["sgd update all"] = st.n_params * 20                                         # read w, vel, g; write w, vel
     hbm_kernels = {k: {"bytes": b, "ms": round(per_call[k], 4), "GB/s": round(b / per_call[k] / 1e6, 1),
                        "frac_of_8TB/s": round(b / per_call[k] / 1e6 / 8000.0, 4)} for k, b in hbm.items() if k in per_call}
 
@@ -226,10 +267,10 @@ def main():
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
         "config": {"workload": workload_name, "batch": N, "conv_gflop_per_step": round(conv_flops / 1e9, 2),
-                   "fc_gflop_per_step": round(fc_flops / 1e9, 2)},
+                   "fc_gflop_per_step": round(fc_total / 1e9, 2)},
         "tflops": round(tflops, 3), "frac_of_mfma_peak": round(tflops / PEAK_TFLOPS[dt], 4),
         "roofline": roofline, "cpu_baseline": cpu,
-        "hbm_kernels": hbm_kernels,
+        "hbm_kernels": hbm_kernels, "kpass_schedule": schedule,
         "per_call_ms": {tag: round(ms, 4) for tag, ms in per_call.items()},
         "kernel_variants": {k: {"calls": v["calls"], "ms": round(v["ms"], 4),
                                 "tflops": round(v["flops"] / v["ms"] / 1e9, 2)} for k, v in groups.items()},

@@ -158,6 +158,17 @@ owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, 
                             float *dw, float *dbias_or_null, void *ws, size_t ws_bytes,
                             void *hip_stream);
 
+/* Optional tuning of a dense shard, as owt_conv_autotune does for a convolution:
+ * times every kernel variant of the three passes (forward; the two halves of
+ * owt_fc_shard_bwd) on the caller's buffers and remembers the fastest for later
+ * owt_fc_shard_* calls with an identical descriptor in this process.  Reads x,
+ * w, bias, y (ReLU mask), dy; writes y, dx_partial, dw, dbias (alpha 1, beta 0).
+ * All of these are required except dbias.  ws must hold the larger of the two
+ * owt_fc_workspace_bytes values.  Blocks until the timing is done. */
+owt_status owt_fc_autotune(const owt_fc_desc *d, const void *x, const void *w, const float *bias, void *y,
+                           const void *dy, void *dx_partial, float *dw, float *dbias_or_null, void *ws,
+                           size_t ws_bytes, void *hip_stream);
+
 /* Max pooling between the convolution layers of the Section 5 model, window
  * win x win (2..15), stride >= 1, no padding: P = floor((H-win)/stride)+1.
  *   y[n,p,q,c] = max_{r,s<win} x[n, p*stride+r, q*stride+s, c]

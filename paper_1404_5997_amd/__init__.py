@@ -24,7 +24,7 @@ EXPORTS = (
     "owt_conv_bwd_filter", "owt_fc_shard_fwd", "owt_fc_shard_bwd", "owt_maxpool_fwd",
     "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe", "owt_conv_autotune",
     "owt_conv_bwd_data_relu_in", "owt_maxpool_bwd_relu", "owt_sgd_momentum_update", "owt_scale_hyperparameters",
-    "owt_logistic_xent",
+    "owt_logistic_xent", "owt_fc_autotune",
 )
 
 
@@ -62,6 +62,7 @@ _lib.owt_conv_bwd_data_relu_in.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _vp, _s
 _lib.owt_maxpool_bwd_relu.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]
 _lib.owt_conv_bwd_filter.argtypes = [_cd, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_conv_autotune.argtypes = [_cd, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
+_lib.owt_fc_autotune.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_fwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_bwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_maxpool_fwd.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp]
@@ -180,6 +181,12 @@ def owt_conv_autotune(desc, pass_, x, w, bias, y, dy, dx, dw, dbias_or_null, ws=
 def owt_fc_shard_fwd(desc, x, w, bias, y, ws=None, stream=None):
     p, n = _ws(ws)
     _check(_lib.owt_fc_shard_fwd(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), p, n, _stream(stream)))
+
+
+def owt_fc_autotune(desc, x, w, bias, y, dy, dx_partial, dw, dbias_or_null, ws=None, stream=None):
+    p, n = _ws(ws)
+    _check(_lib.owt_fc_autotune(ctypes.byref(desc), _ptr(x), _ptr(w), _ptr(bias), _ptr(y), _ptr(dy), _ptr(dx_partial),
+                                _ptr(dw), _ptr(dbias_or_null), p, n, _stream(stream)))
 
 
 def owt_fc_shard_bwd(desc, x, w, y_or_null, dy, alpha, beta, dx_partial_or_null, dw, dbias_or_null,

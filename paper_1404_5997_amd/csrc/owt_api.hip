@@ -743,7 +743,7 @@ owt_status owt_fc_shard_fwd(const owt_fc_desc *d, const void *x, const void *w, 
     if (d->flags & OWT_BIAS) OWT_TRY(check_ptr(bias, "bias"));
     GemmParams p; memset(&p, 0, sizeof(p));
     p.a = x; p.b = w; p.out = y; p.bias = bias; p.flags = d->flags;
-    return conv_pass(g, OWT_PASS_FWD, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, false);
+    return conv_pass(g, OWT_PASS_FWD, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, true);
 }
 
 owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, const void *y_or_null,
@@ -765,12 +765,33 @@ owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, 
     if (dx_partial_or_null) {
         GemmParams p; memset(&p, 0, sizeof(p));
         p.a = dy; p.b = w; p.out = dx_partial_or_null; p.flags = d->flags; p.mask = mask;
-        OWT_TRY(conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, false));
+        OWT_TRY(conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, true));
     }
     GemmParams p; memset(&p, 0, sizeof(p));
     p.a = dy; p.b = x; p.out = dw; p.flags = d->flags; p.alpha = alpha; p.beta = beta;
     p.dbias = dbias_or_null; p.mask = mask;
-    return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, p, true, ws, ws_bytes, (hipStream_t)hip_stream, false);
+    return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, p, true, ws, ws_bytes, (hipStream_t)hip_stream, true);
+}
+
+owt_status owt_fc_autotune(const owt_fc_desc *d, const void *x, const void *w, const float *bias, void *y,
+                           const void *dy, void *dx_partial, float *dw, float *dbias_or_null, void *ws,
+                           size_t ws_bytes, void *hip_stream)
+{
+    // the shard is the convolution with H = W = R = S = 1 on [N, I] -> [N, O_local]: tune that geometry
+    Geom g; int ol;
+    OWT_TRY(check_fc(d, g, ol));
+    owt_conv_desc c;
+    memset(&c, 0, sizeof(c));
+    c.N = d->N; c.C = d->I; c.H = c.W = 1; c.K = ol; c.R = c.S = 1; c.stride_h = c.stride_w = 1;
+    c.dtype = d->dtype; c.flags = d->flags;
+    const size_t need_f = owt_fc_workspace_bytes(d, OWT_PASS_FWD), need_b = owt_fc_workspace_bytes(d, OWT_PASS_BWD_DATA);
+    if (ws_bytes < (need_f > need_b ? need_f : need_b))
+        return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need_f > need_b ? need_f : need_b, ws_bytes);
+    OWT_TRY(owt_conv_autotune(&c, OWT_PASS_FWD, x, w, bias, y, nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, hip_stream));
+    OWT_TRY(owt_conv_autotune(&c, OWT_PASS_BWD_DATA, nullptr, w, nullptr, y, dy, dx_partial, nullptr, nullptr, ws, ws_bytes,
+                              hip_stream));
+    return owt_conv_autotune(&c, OWT_PASS_BWD_FILTER, x, w, nullptr, y, dy, nullptr, dw, dbias_or_null, ws, ws_bytes,
+                             hip_stream);
 }
 
 }  // extern "C"

@@ -14,7 +14,7 @@ import torch
 
 from . import (OWT_BF16, OWT_BIAS, OWT_F32, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER, OWT_PASS_FWD, OWT_RELU,
                conv_desc, fc_desc, owt_conv_autotune, owt_conv_bwd_data, owt_conv_bwd_data_relu_in, owt_conv_bwd_filter, owt_conv_fwd, owt_conv_workspace_bytes,
-               owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_logistic_xent, owt_maxpool_bwd_relu,
+               owt_fc_autotune, owt_fc_shard_bwd, owt_fc_shard_fwd, owt_fc_workspace_bytes, owt_logistic_xent, owt_maxpool_bwd_relu,
                owt_maxpool_fwd, owt_sgd_momentum_update)
 
 
@@ -92,6 +92,8 @@ class ConvStack:
         the whole array.  bf16 stacks read a bf16 copy of the weights that the update rewrites."""
         off, slots = 0, []
         for e in self.L + self.F:
+            if self.F and e is self.F[0]:
+                self.fc_offset = off
             for key, shape in (("w", e["wshape"]), ("b", e["bshape"])):
                 n = 1
                 for v in shape:
@@ -99,6 +101,8 @@ class ConvStack:
                 slots.append((e, key, shape, off, n))
                 off += (n + 7) // 8 * 8
         self.n_params = off
+        if not self.F:
+            self.fc_offset = off
         self.params = torch.zeros((off,), device=dev, dtype=torch.float32)
         self.grads = torch.zeros((off,), device=dev, dtype=torch.float32)
         self.vel = torch.zeros((off,), device=dev, dtype=torch.float32)
@@ -111,12 +115,15 @@ class ConvStack:
             else:
                 e[key] = e[key + "32"]
 
-    def update(self, mu, eps, omega, gscale=-1.0):
-        """Weight update rule of Section 5 over every parameter of the worker, one launch.  The
-        gradients in self.grads are batch means of a loss (alpha = 1/N), so the default gscale = -1
-        descends."""
-        self._run("sgd update", owt_sgd_momentum_update, self.n_params, self.params, self.vel, self.grads, mu, eps,
-                  omega, gscale, self.params_bf16)
+    def update(self, mu, eps, omega, gscale=-1.0, part="all"):
+        """Weight update rule of Section 5 over every parameter of the worker (or only the convolution
+        / dense part of the array), one launch.  The gradients in self.grads are batch means of a loss
+        (alpha = 1/N), so the default gscale = -1 descends."""
+        lo, hi = {"all": (0, self.n_params), "conv": (0, self.fc_offset), "fc": (self.fc_offset, self.n_params)}[part]
+        if hi > lo:
+            self._run("sgd update " + part, owt_sgd_momentum_update, hi - lo, self.params[lo:hi], self.vel[lo:hi],
+                      self.grads[lo:hi], mu, eps, omega, gscale,
+                      None if self.params_bf16 is None else self.params_bf16[lo:hi])
 
     # ------------------------------------------------------------------ setup
     def load(self, x, ws, bs, fc_ws=None, fc_bs=None, fc_peers=None):
@@ -154,7 +161,7 @@ class ConvStack:
         else:
             self.hook(tag, lambda: fn(*args))
 
-    def forward(self):
+    def forward_conv(self):
         cur = self.x
         for li, e in enumerate(self.L):
             N, C, H, W, K, R, st, pad, P, Q = e["geom"]
@@ -164,27 +171,53 @@ class ConvStack:
             if e["pool"]:
                 self._run("pool%d fwd" % (li + 1), owt_maxpool_fwd, N, P, Q, K, self.win, self.pst, self.code, e["y"], e["a"], e["am"])
                 cur = e["a"]
+        return cur
+
+    def forward_fc(self, feats, ws=None):
+        """The worker's dense column shards on one batch of last-stage convolution activations
+        feats [N, I] (Section 4, forward step 3)."""
+        ws = self.ws if ws is None else ws
+        cur = feats
         for i, f in enumerate(self.F):
             if i == 0:
-                f["x"] = cur.view(self.N, -1)
+                f["x"] = feats
             else:
                 prev = self.F[i - 1]
                 f["x"][:, :prev["O"]].copy_(prev["y"])        # own columns (rank 0) beside the peers'
-            self._run("fc%d fwd" % (i + 1), owt_fc_shard_fwd, f["desc"], f["x"], f["w"], f["b"], f["y"], self.ws)
+            self._run("fc%d fwd" % (i + 1), owt_fc_shard_fwd, f["desc"], f["x"], f["w"], f["b"], f["y"], ws)
             cur = f["y"]
         return cur
 
-    def backward(self):
-        if self.labels is not None:
+    def backward_fc(self, dx_feats, labels=None, alpha=None, beta=None, ws=None):
+        """Backward through the dense shards for the batch forward_fc() last ran on (Section 4, backward
+        step 1): this worker's addend of the gradient of the convolution activations goes to dx_feats."""
+        ws = self.ws if ws is None else ws
+        alpha = self.alpha if alpha is None else alpha
+        beta = self.beta if beta is None else beta
+        if labels is not None:
             f = self.F[-1]
             self._run("fc%d logistic xent" % len(self.F), owt_logistic_xent, self.N, f["O"], 0, self.code, f["y"],
-                      self.labels, 1.0, self.loss, f["dy"])
+                      labels, 1.0, self.loss, f["dy"])
         for i in range(len(self.F) - 1, -1, -1):
             f = self.F[i]
+            dx = dx_feats if i == 0 else f["dx"]
             self._run("fc%d bwd" % (i + 1), owt_fc_shard_bwd, f["desc"], f["x"], f["w"],
-                      f["y"] if f["relu"] else None, f["dy"], self.alpha, self.beta, f["dx"], f["dw"], f["db"], self.ws)
+                      f["y"] if f["relu"] else None, f["dy"], alpha, beta, dx, f["dw"], f["db"], ws)
             if i > 0:   # the slice of dx_partial that belongs to this worker's own columns
                 self.F[i - 1]["dy"].copy_(f["dx"][:, :self.F[i - 1]["O"]])
+
+    def forward(self):
+        cur = self.forward_conv()
+        if self.F:
+            cur = self.forward_fc(cur.view(self.N, -1))
+        return cur
+
+    def backward(self):
+        if self.F:
+            self.backward_fc(self.F[0]["dx"], self.labels)
+        self.backward_conv()
+
+    def backward_conv(self):
         for li in range(len(self.L) - 1, -1, -1):
             e = self.L[li]
             N, C, H, W, K, R, st, pad, P, Q = e["geom"]
@@ -211,6 +244,52 @@ class ConvStack:
     def step(self):
         self.forward()
         self.backward()
+
+    def step_kpass(self, peer_feats, labels=None, per_pass_update=None, overlap=False):
+        """One worker's step under scheme (b)/(c) of Section 4 with K = 1 + len(peer_feats) workers:
+        convolution forward on the own batch; K forward+backward iterations of the dense shards, the
+        first on the own batch's last-stage activations and the others on peer_feats[j] ([N, I] device
+        tensors standing in for what the other workers send); then convolution backward from the own
+        batch's gradient.  The addends of the peers' activation gradients land in self.peer_dx (they
+        would be sent back to their workers).
+
+        per_pass_update = None: the dense weight gradients accumulate over the K iterations with
+        alpha = 1/(N*K) (the whole step is then synchronous SGD on N*K examples, Section 4.2).
+        per_pass_update = (mu, eps, omega): the dense weights are updated after every iteration from that
+        iteration's batch-N gradient (the variable batch size of Section 4.2).
+        overlap: run the iterations on the peers' batches on a second stream beside the convolution
+        backward pass (they do not depend on each other)."""
+        assert self.F and self.hook is None
+        K = 1 + len(peer_feats)
+        if labels is None:
+            labels = [self.labels] * K
+        if not hasattr(self, "peer_dx"):
+            self.peer_dx = torch.empty_like(peer_feats[0])
+            self.side = torch.cuda.Stream(device=self.x.device)
+            self.ws_side = torch.empty_like(self.ws)
+
+        def iteration(j, feats, dx, ws):
+            self.forward_fc(feats, ws)
+            if per_pass_update is None:
+                self.backward_fc(dx, labels[j], 1.0 / (self.N * K), 0.0 if j == 0 else 1.0, ws)
+            else:
+                self.backward_fc(dx, labels[j], 1.0 / self.N, 0.0, ws)
+                self.update(*per_pass_update, part="fc")
+
+        own = self.forward_conv().view(self.N, -1)
+        iteration(0, own, self.F[0]["dx"], self.ws)
+        main = torch.cuda.current_stream()
+        if overlap:
+            self.side.wait_stream(main)
+            with torch.cuda.stream(self.side):
+                for j, feats in enumerate(peer_feats, start=1):
+                    iteration(j, feats, self.peer_dx, self.ws_side)
+            self.backward_conv()
+            main.wait_stream(self.side)
+        else:
+            for j, feats in enumerate(peer_feats, start=1):
+                iteration(j, feats, self.peer_dx, self.ws)
+            self.backward_conv()
 
     def capture(self):
         """Record one step into a HIP graph; replay() then runs it with a single launch from the host
@@ -240,6 +319,9 @@ class ConvStack:
             if dx is not None:
                 owt_conv_autotune(d, OWT_PASS_BWD_DATA, None, e["w"], None, e["y"], e["dy"], dx, None, None, self.ws)
             owt_conv_autotune(d, OWT_PASS_BWD_FILTER, e["x"], e["w"], None, e["y"], e["dy"], None, e["dw"], e["db"], self.ws)
+        for i, f in enumerate(self.F):
+            owt_fc_autotune(f["desc"], f["x"], f["w"], f["b"], f["y"], f["dy"], self.F[0]["dx"] if i == 0 else f["dx"],
+                            f["dw"], f["db"], self.ws)
         self.step()
 
     # ----------------------------------------------------------- work counters

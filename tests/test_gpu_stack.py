@@ -245,3 +245,87 @@ def test_hip_graph_replay_of_a_step_equals_eager_launches():
         st.step()                                   # eager work between replays
         torch.cuda.synchronize()
         assert torch.equal(st.grads, ref_g)
+
+
+def _kpass_inputs(st, K, seed):
+    g = np.random.default_rng(si.BASE_SEED + seed)
+    I0 = st.F[0]["I"]
+    peer = [np.maximum(g.standard_normal((st.N, I0), dtype=np.float32), 0) * np.float32(0.05) for _ in range(K - 1)]
+    labels = [g.integers(0, 1000, size=st.N).astype(np.int32) for _ in range(K)]
+    dev = [torch.from_numpy(p).cuda() for p in peer]
+    lab = [torch.from_numpy(l).cuda() for l in labels]
+    return peer, labels, dev, lab
+
+
+def _oracle_fc_chain(feats, fws, fbs, peers, labels, alpha):
+    """Free-running oracle pass through the three dense shards on `feats` (any number of rows; the
+    peers' hidden columns are repeated per block of N rows).  Returns dx of the features and [(dw, db)]."""
+    rows = feats.shape[0]
+    reps = rows // peers[0].shape[0]
+    xs, ys, cur = [], [], feats
+    for i, spec in enumerate(si.FC_LAYERS):
+        if i > 0:
+            cur = np.concatenate([ys[-1], np.tile(peers[i - 1], (reps, 1))], axis=1)
+        xs.append(cur)
+        ys.append(oracle.fc_fwd(cur, fws[i], fbs[i], spec["relu"]))
+    loss, dtop = oracle.logistic_xent(ys[-1], labels, 0, 1.0)
+    grads = [None] * 3
+    for i in range(2, -1, -1):
+        dx, dw, db = oracle.fc_bwd(xs[i], fws[i], dtop, y=ys[i] if si.FC_LAYERS[i]["relu"] else None, alpha=alpha)
+        grads[i] = (dw, db)
+        dtop = dx[:, :ys[i - 1].shape[1]] if i > 0 else dx
+    return dtop, grads, loss
+
+
+@pytest.mark.parametrize("overlap", [False, True])
+def test_kpass_dense_schedule_accumulating_equals_one_big_batch(overlap):
+    # Section 4 scheme (b) with K = 8: eight forward+backward iterations of the dense shards, gradients
+    # accumulated (beta = 1) with alpha = 1/(8*128), must equal ONE pass over the 1024 examples at once
+    # (Section 4.2: the schedule is synchronous SGD on 128K examples).  The oracle does the big batch.
+    K = 8
+    st, x, ws, bs, g, (fws, fbs, peers) = build_stack(4, 128, "f32", with_fc=True)
+    peer, labels, dev, lab = _kpass_inputs(st, K, 4200)
+    st.step_kpass(dev, lab, None, overlap)
+    torch.cuda.synchronize()
+    own = to_host(st.F[0]["x"]) if False else to_host(st.L[-1]["a"]).reshape(st.N, -1)
+    big = np.concatenate([own] + peer, axis=0)
+    dfeat, grads, _ = _oracle_fc_chain(big, fws, fbs, peers, np.concatenate(labels), 1.0 / (st.N * K))
+    for i, f in enumerate(st.F):
+        e1 = assert_close(to_host(f["dw"]), grads[i][0], "f32", "fc%d dw accumulated over %d passes" % (i + 1, K))
+        e2 = assert_close(to_host(f["db"]), grads[i][1], "f32", "fc%d db accumulated" % (i + 1))
+        say("  fc%d accumulated dw %.2e db %.2e" % (i + 1, e1, e2))
+    assert_close(to_host(st.L[-1]["da"]).reshape(st.N, -1), dfeat[:st.N], "f32", "gradient of the own batch's activations")
+    assert_close(to_host(st.peer_dx), dfeat[-st.N:], "f32", "gradient addend for the last peer's batch")
+    # the convolution backward pass ran from the own batch's gradient: same bits as running it again
+    conv_g = st.grads[:st.fc_offset].clone()
+    assert float(conv_g.abs().max()) > 0
+    st.backward_conv()
+    torch.cuda.synchronize()
+    assert torch.equal(conv_g, st.grads[:st.fc_offset])
+
+
+@pytest.mark.parametrize("overlap", [False, True])
+def test_kpass_dense_schedule_with_an_update_after_every_pass(overlap):
+    # the variable batch size of Section 4.2: the dense weights move after each of the K iterations
+    # (batch-128 gradient each time); the oracle replays the same sequence with its own arithmetic
+    K = 4
+    st, x, ws, bs, g, (fws, fbs, peers) = build_stack(4, 128, "f32", with_fc=True)
+    peer, labels, dev, lab = _kpass_inputs(st, K, 4300)
+    mu, eps, omega = 0.9, 0.01, 0.0005
+    p_conv0 = st.params[:st.fc_offset].clone()
+    st.step_kpass(dev, lab, (mu, eps, omega), overlap)
+    torch.cuda.synchronize()
+    own = to_host(st.L[-1]["a"]).reshape(st.N, -1)
+    w = [fw.copy() for fw in fws]; b = [fb.copy() for fb in fbs]
+    vw = [np.zeros_like(a) for a in w]; vb = [np.zeros_like(a) for a in b]
+    for j, feats in enumerate([own] + peer):
+        _, grads, _ = _oracle_fc_chain(feats, w, b, peers, labels[j], 1.0 / st.N)
+        for i in range(3):
+            w[i], vw[i] = oracle.sgd_momentum(w[i], vw[i], grads[i][0], mu, eps, omega, -1.0)
+            b[i], vb[i] = oracle.sgd_momentum(b[i], vb[i], grads[i][1], mu, eps, omega, -1.0)
+    for i, f in enumerate(st.F):
+        e1 = assert_close(to_host(f["w32"]), w[i], "f32", "fc%d weights after %d updates" % (i + 1, K))
+        e2 = assert_close(to_host(f["b32"]), b[i], "f32", "fc%d biases after %d updates" % (i + 1, K))
+        say("  fc%d weights %.2e biases %.2e" % (i + 1, e1, e2))
+        assert e1 < 1e-5
+    assert torch.equal(p_conv0, st.params[:st.fc_offset])        # convolution weights wait for the end of the step
