@@ -30,6 +30,7 @@ def _units():
                           ["-DOWT_INST_PASS=%d" % ps, "-DOWT_INST_BF16=%d" % bf]))
     for ps, pname in ((0, "fwd"), (1, "data")):
         units.append(("dconv16_%s.o" % pname, "dconv_bf16_inst.hip", ["-DOWT_INST_PASS=%d" % ps]))
+    units.append(("dfilter16.o", "dfilter_bf16_inst.hip", []))
     for bf in (0, 1):
         units.append(("sconv_%s.o" % ("bf16" if bf else "f32"), "sconv_inst.hip", ["-DOWT_INST_BF16=%d" % bf]))
     for bf in (0, 1):

@@ -53,7 +53,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -113,6 +113,20 @@ static bool dfilter_fits(const Geom &g, int variant, int &taps, int &groups)
     else return false;
     const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q;
     const long span = 31 + (31 / g.Q + 1) * (Wp - g.Q) + (31 / PQ + 1) * (Hp - g.P) * Wp;
+    const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
+    return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
+}
+
+// The same for the bf16-MFMA variant (64-pixel chunks, 16-byte pieces: C and K multiples of 8).
+static bool dfilter16_fits(const Geom &g, int variant, int &taps, int &groups)
+{
+    const DFilter16Variant &v = kDFilter16Variants[variant];
+    if (!g.bf16 || g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W || g.C % 8 || g.K % 8) return false;
+    if (g.R * g.S == v.tmax) { taps = g.R * g.S; groups = 1; }
+    else if (g.S == v.tmax) { taps = g.S; groups = g.R; }
+    else return false;
+    const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q, last = kDFilter16BP - 1;
+    const long span = last + (last / g.Q + 1) * (Wp - g.Q) + (last / PQ + 1) * (Hp - g.P) * Wp;
     const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
     return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
 }
@@ -216,10 +230,10 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
     static const long kSplits[] = {1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256};
     // split counts to try for `tiles` output tiles: the fixed ladder plus the counts that fill one, two
     // or three rounds of the chip's work-group slots exactly (256 CUs x 2 resident work-groups)
-    auto split_ladder = [&](long tiles) {
+    auto split_ladder = [&](long tiles, long slots = 512) {
         std::vector<long> v(kSplits, kSplits + sizeof(kSplits) / sizeof(kSplits[0]));
         for (long rounds = 1; rounds <= 3; rounds++)
-            if (512 * rounds / tiles >= 1) v.push_back(512 * rounds / tiles);
+            if (slots * rounds / tiles >= 1) v.push_back(slots * rounds / tiles);
         std::sort(v.begin(), v.end());
         v.erase(std::unique(v.begin(), v.end()), v.end());
         return v;
@@ -332,6 +346,38 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             }
         }
     }
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !getenv("OWT_NO_BF16_MFMA")) {
+        for (int v = 0; v < 3; v++) {
+            int taps, groups;
+            if (force_tile >= 0 && force_tile != v) continue;
+            if (!dfilter16_fits(g, v, taps, groups)) continue;
+            const DFilter16Variant &dv = kDFilter16Variants[v];
+            const long KT = 32 * dv.KB * dv.WK, CT = 32 * dv.WC;
+            const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, kDFilter16BP);
+            for (long s0 : split_ladder(tm * ctl * groups, 1024 / (dv.WK * dv.WC))) {   // one wavefront per SIMD
+                long s = s0;
+                if (force_split > 0) s = force_split < steps ? force_split : steps;
+                else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 1280)) break;
+                const long per = cdiv(steps, s), splits = cdiv(steps, per);
+                Launch l; memset(&l, 0, sizeof(l));
+                l.kind = KIND_DFILTER16; l.tile = v; l.splits = (int)splits; l.steps = (int)steps;
+                l.steps_per_split = (int)per; l.tiles_m = (int)tm; l.tiles_n = (int)(ctl * groups);
+                l.taps = taps; l.groups = groups; l.ctiles = (int)ctl;
+                if (splits > 1) {
+                    l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                    l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+                }
+                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, 4 / (dv.WK * dv.WC),
+                                    (double)KT * CT * kDFilter16BP * taps * per / 5.0, 1.2,
+                                    splits, dm.M, dm.Ncols);
+                bool dup = false;
+                for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
+                if (!dup && (l.partial_bytes <= kMaxPartialBytes || force_split > 0) &&
+                    (force_split > 0 || tm * ctl * groups * splits >= 64 || s0 == 256)) out.push_back(l);
+                if (force_split > 0) break;
+            }
+        }
+    }
     // the gather kernel is the fallback of the stride-1 forward / backward-data kernel, and an
     // alternative worth timing next to the direct filter-gradient kernel
     const bool have_direct = !out.empty() && (out[0].kind == KIND_DIRECT || out[0].kind == KIND_DIRECT16);
@@ -419,6 +465,10 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         sfilter_geom(g, sg);
         sg.units_per_wg = l.steps_per_split;
         e = bf ? owt_launch_sfilter_bf16(p, sg, l.tiles_m, s) : owt_launch_sfilter_f32(p, sg, l.tiles_m, s);
+    } else if (l.kind == KIND_DFILTER16) {
+        p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
+        p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
+        e = owt_launch_dfilter16(l.tile, p, s);
     } else if (l.kind == KIND_DFILTER) {
         p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
         p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
@@ -451,6 +501,12 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     if (l.kind == KIND_SFILTER)
         return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d threads%ld", pn[pass], ds, l.splits, l.tiles_m,
                         l.splits, (long)l.tiles_m * l.splits * kSFilterNT);
+    if (l.kind == KIND_DFILTER16) {
+        const DFilter16Variant &v = kDFilter16Variants[l.tile];
+        return snprintf(buf, n, "dfilter16 %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
+                        32 * v.KB * v.WK, 32 * v.WC, l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits,
+                        (long)l.tiles_m * l.tiles_n * l.splits * 64 * v.WK * v.WC);
+    }
     if (l.kind == KIND_DFILTER) {
         const DFilterVariant &v = kDFilterVariants[l.tile];
         return snprintf(buf, n, "dfilter %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds, 32 * v.WK,

@@ -170,6 +170,27 @@ def test_bf16_mfma_direct_kernel(tile, split):
             os.environ.pop(k, None)
 
 
+@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (0, 3), (1, 4), (2, 7)])
+def test_bf16_mfma_filter_gradient_kernel(variant, split):
+    # bf16 storage, stride 1, "same" padding, channels and filters multiples of 8: the filter gradient runs on
+    # the bf16 MFMA, one filter row per work-group (3-tap variants 0 and 2, 5-tap variant 1)
+    m = owt()
+    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(variant), str(split)
+    try:
+        shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25))] \
+            if variant == 1 else \
+            [((4, 72, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
+             ((3, 8, 6, 11, 8, 3, 3, 1), dict(relu=False, alpha=1.0 / 3, beta=1.0))]
+        for (N, C, H, W, K, R, S, pad), kw in shapes:
+            d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_BF16, m.OWT_BIAS | m.OWT_RELU)
+            assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("dfilter16"), \
+                m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER)
+            layer_parity(N, C, H, W, K, R, S, 1, pad, dt="bf16", seed=500 + 10 * variant + split, **kw)
+    finally:
+        for k in ("OWT_TILE", "OWT_SPLITK"):
+            os.environ.pop(k, None)
+
+
 @pytest.mark.parametrize("shape,split", [
     ((5, 4, 23, 20, 8, 7, 7, 4, 2), 3), ((2, 3, 24, 24, 72, 7, 7, 4, 3), 0), ((3, 3, 36, 28, 64, 11, 11, 4, 2), 5),
     ((2, 8, 17, 12, 20, 5, 3, (2, 2), (2, 1)), 2), ((2, 3, 224, 224, 64, 11, 11, 4, 2), 0)])
