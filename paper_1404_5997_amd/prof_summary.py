@@ -30,6 +30,8 @@ def family(name):
         return "dconv16 " + ("fwd" if "EpiFwd" in n else "bwd_data")
     if n.startswith("dconv_kernel"):
         return "dconv " + ("fwd" if "EpiFwd" in n else "bwd_data")
+    if n.startswith("dfilter16_kernel"):
+        return "dfilter16 bwd_filter"
     if n.startswith("dfilter_kernel"):
         return "dfilter bwd_filter"
     if n.startswith("sfilter_kernel"):
