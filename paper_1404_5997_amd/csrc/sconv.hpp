@@ -61,7 +61,8 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     const T *xsrc = (const T *)p.a;
     const int row_f4 = g.W * g.C / 4, panel_f4 = sg.ROWS * row_f4;
     const int img_off = g.pw * g.C + sg.LPAD;
-    float4 preg[PNP], breg[2];
+    constexpr int BPASS = (KB + NT / BQ - 1) / (NT / BQ);       // passes of the filter-slice loader
+    float4 preg[PNP], breg[BPASS];
     const int bq = tid % BQ, bl0 = tid / BQ;                    // filter-slice loader: quad, filter line
     constexpr int BLPP = NT / BQ;                               // lines per pass (51 for 512 threads)
 
@@ -87,7 +88,7 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     };
     auto load_b = [&](int step) {
 #pragma unroll
-        for (int it = 0; it < 2; it++) {
+        for (int it = 0; it < BPASS; it++) {
             const int line = bl0 + it * BLPP, k = k0 + line;
             breg[it] = (line < KB && k < g.K) ? *(const float4 *)(w2 + (size_t)k * sg.KSLOTS + step * BK + bq * 4)
                                               : make_float4(0.f, 0.f, 0.f, 0.f);
@@ -95,7 +96,7 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     };
     auto store_b = [&](float *buf) {
 #pragma unroll
-        for (int it = 0; it < 2; it++) {
+        for (int it = 0; it < BPASS; it++) {
             const int line = bl0 + it * BLPP;
             if (line < KB) *(float4 *)(buf + line * WP + bq * 4) = breg[it];
         }
