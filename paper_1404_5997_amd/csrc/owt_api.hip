@@ -132,8 +132,8 @@ static bool dfilter16_fits(const Geom &g, int variant, int &taps, int &groups)
 }
 
 // Geometry of the small-channel strided filter-gradient kernel; false when it does not apply
-// (needs window starts and image rows that are multiples of 4 floats, at most 14 blocks of 32
-// slots, and an LDS footprint that leaves room for two work-groups per CU).
+// (needs window starts and image rows that are multiples of 4 floats, at most 16 blocks of 32
+// slots (four accumulators per wavefront in each of four column groups), at most 150 KB of LDS).
 static bool sfilter_geom(const Geom &g, SFilterGeom &sg)
 {
     if ((g.sw * g.C) % 4 || (g.W * g.C) % 4 || g.K % 4) return false;

@@ -106,3 +106,13 @@ def test_scale_hyperparameters_host_call_matches_the_papers_example(m):
     assert abs(o2 - vals["wd_example_omega_scaled"]) < 5e-11
     with pytest.raises(m.OwtError):
         m.owt_scale_hyperparameters(0.0, 0.01, 0.0005)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # this build runs one worker on one GPU: bench.py must say so and exit before touching a device
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode == 2
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
