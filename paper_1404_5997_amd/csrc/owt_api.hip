@@ -7,6 +7,7 @@
 
 #include "owt_host.hpp"
 #include "sconv.hpp"
+#include "sconv_bf16.hpp"
 #include "sfilter.hpp"
 
 namespace owt {
@@ -53,7 +54,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -99,6 +100,32 @@ static long direct_panel_rows(const Geom &g, int pass, const PassDims &dm, long 
         if (rows > need) need = rows;
     }
     return need;
+}
+
+// Geometry of the bf16-MFMA small-channel strided forward kernel; false when it does not apply (bf16
+// storage, window starts and image rows that are multiples of 4 values, K a multiple of 4, the filter
+// bank of 64 filters plus one band of rows within 150 KB of LDS).
+static bool sconv16_geom(const Geom &g, SConv16Geom &sg)
+{
+    if (!g.bf16 || (g.sw * g.C) % 4 || (g.W * g.C) % 4 || g.C > 16 || g.K % 4 || (g.sh == 1 && g.sw == 1)) return false;
+    sg.SEG = g.S * g.C;
+    sg.LPAD = (4 - (g.pw * g.C) % 4) % 4;
+    sg.SLOTS = (sg.SEG + sg.LPAD + 7) & ~7;
+    sg.OCT = sg.SLOTS / 8;
+    sg.NG = ((g.R * sg.OCT + 3) / 4) * 2;          // groups of 16 slots, an even number of them
+    sg.KSLOTS = sg.NG * 16;
+    sg.WP = sg.KSLOTS + 8;
+    const int a = g.pw * g.C + sg.LPAD + g.W * g.C, b = (g.Q - 1) * g.sw * g.C + sg.SLOTS;
+    sg.PITCH = ((a > b ? a : b) + 7) & ~7;
+    sg.ROWS = (kSConv16TP - 1) * g.sh + g.R;
+    // the padded tail of the reduction (up to 3 octets) reads past filter row R-1: those panel rows exist and stay zero
+    sg.ZROWS = sg.ROWS + 1 + (3 + sg.OCT - 1) / sg.OCT;
+    sg.MPIX = kSConv16TP * g.Q;
+    sg.units_per_image = (g.P + kSConv16TP - 1) / kSConv16TP;
+    sg.units = g.N * sg.units_per_image;
+    const size_t lds = ((size_t)64 * sg.WP + (size_t)2 * sg.ZROWS * sg.PITCH) * 2;     // filter bank + two bands
+    return sg.OCT >= 2 && sg.MPIX <= 256 && lds <= 150 * 1024 &&
+           (long)sg.ROWS * (g.W * g.C / 4) <= (long)(kSConv16NT / 2) * kSConv16PNP;
 }
 
 // Tap grouping and panel size of the direct filter-gradient kernel for one variant; false when it
@@ -292,6 +319,25 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (force_split > 0) break;
         }
     }
+    SConv16Geom s16g;
+    if (pass == OWT_PASS_FWD && !no_direct && !getenv("OWT_NO_BF16_MFMA") && sconv16_geom(g, s16g)) {
+        const long ktiles = cdiv(g.K, 64);
+        for (long target : {256L, 512L}) {
+            long wgs = target / ktiles > 0 ? target / ktiles : 1;
+            if (force_split > 0) wgs = force_split;
+            if (wgs > s16g.units) wgs = s16g.units;
+            const long per = cdiv(s16g.units, wgs), n = cdiv(s16g.units, per);
+            Launch l; memset(&l, 0, sizeof(l));
+            l.kind = KIND_SCONV16; l.splits = 1; l.steps = s16g.units; l.steps_per_split = (int)per;
+            l.tiles_m = (int)ktiles; l.tiles_n = (int)n;
+            l.partial_bytes = pad256((size_t)g.K * s16g.KSLOTS * 2);        // the re-laid-out filters
+            l.cost = model_cost(ktiles * n, 4, 1, 256.0 * 64 * s16g.KSLOTS * per / 6.0, 1.0, 1, dm.M, dm.Ncols);
+            bool dup = false;
+            for (const Launch &o : out) dup |= o.kind == l.kind && o.tiles_n == l.tiles_n;
+            if (!dup) out.push_back(l);
+            if (force_split > 0) break;
+        }
+    }
     SFilterGeom sfg;
     if (pass == OWT_PASS_BWD_FILTER && !no_direct && (g.sh > 1 || g.sw > 1) && sfilter_geom(g, sfg)) {
         const long ktiles = cdiv(g.K, 64);
@@ -453,6 +499,12 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
     if (l.kind == KIND_DIRECT16) {
         dconv_frame(g, pass, p);
         e = pass == OWT_PASS_FWD ? owt_launch_dconv16_fwd(l.tile, l.pr, p, s) : owt_launch_dconv16_data(l.tile, l.pr, p, ws, s);
+    } else if (l.kind == KIND_SCONV16) {
+        SConv16Geom sg;
+        sconv16_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        p.splits = 1; p.partial = nullptr;
+        e = owt_launch_sconv16(p, sg, l.tiles_m, l.tiles_n, ws, s);
     } else if (l.kind == KIND_SCONV) {
         SConvGeom sg;
         sconv_geom(g, sg);
@@ -495,6 +547,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     // figure profilers list as its grid size)
     static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
     const char *ds = dt == OWT_BF16 ? "bf16" : "f32";
+    if (l.kind == KIND_SCONV16)
+        return snprintf(buf, n, "sconv16 %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConv16TP, l.tiles_m, l.tiles_n,
+                        (long)l.tiles_m * l.tiles_n * kSConv16NT);
     if (l.kind == KIND_SCONV)
         return snprintf(buf, n, "sconv %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConvTP, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConvNT);
@@ -637,7 +692,7 @@ int owt_selftest_host(void)
             if (c.empty()) { fail(OWT_EINVAL, "no candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 3; }
             const size_t bound = max_workspace(g, pass, dm, pass == OWT_PASS_BWD_FILTER);
             for (const Launch &l : c) {
-                const long parts = l.kind == KIND_SCONV ? l.tiles_n : l.splits;   // who shares the steps
+                const long parts = (l.kind == KIND_SCONV || l.kind == KIND_SCONV16) ? l.tiles_n : l.splits;   // who shares the steps
                 if (l.splits < 1 || parts * l.steps_per_split < l.steps ||
                     (parts - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
                     ((l.kind == KIND_DIRECT || l.kind == KIND_DIRECT16) && (l.pr > 384 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {

@@ -63,14 +63,16 @@ struct bf16_t { uint16_t bits; };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
 
-// fp32 -> bf16, round to nearest even; NaN stays NaN.
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+// fp32 -> bf16, round to nearest even; NaN stays NaN.  gfx950 has the conversion in hardware
+// (v_cvt_pk_bf16_f32, two values per instruction).
+typedef __bf16 owt_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float owt_f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7f800000u) == 0x7f800000u && (u & 0x007fffffu)) return (uint16_t)((u >> 16) | 0x0040u);
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    const owt_f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, owt_bf16x2));
 }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return (uint16_t)(f32x2_to_bf16x2(f, 0.f) & 0xffffu); }
 
 __device__ __forceinline__ float4 load4(const float *p, int off) { return *(const float4 *)(p + off); }
 __device__ __forceinline__ float4 load4(const bf16_t *p, int off)
@@ -90,7 +92,7 @@ __device__ __forceinline__ void store2(float *p, size_t off, float v0, float v1)
 }
 __device__ __forceinline__ void store2(bf16_t *p, size_t off, float v0, float v1)
 {
-    *(uint32_t *)(p + off) = (uint32_t)f32_to_bf16(v0) | ((uint32_t)f32_to_bf16(v1) << 16);
+    *(uint32_t *)(p + off) = f32x2_to_bf16x2(v0, v1);
 }
 
 }  // namespace owt

@@ -58,6 +58,10 @@ constexpr DFilter16Variant kDFilter16Variants[3] = {{1, 4, 4, 3, 128}, {2, 2, 2,
 constexpr int kDFilter16BP = 64;
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 
+// bf16-MFMA small-channel strided forward kernel (sconv_bf16_inst.hip); w2 = K x KSLOTS bf16 values of workspace.
+struct SConv16Geom;
+hipError_t owt_launch_sconv16(const GemmParams &, const SConv16Geom &, int ktiles, int nwg, void *w2, hipStream_t);
+
 // Small-channel strided filter-gradient kernel (sfilter_inst.hip).
 struct SFilterGeom;
 hipError_t owt_launch_sfilter_f32(const GemmParams &, const SFilterGeom &, int ktiles, hipStream_t);
