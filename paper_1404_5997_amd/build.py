@@ -32,6 +32,7 @@ def _units():
         units.append(("dconv16_%s.o" % pname, "dconv_bf16_inst.hip", ["-DOWT_INST_PASS=%d" % ps]))
     units.append(("dfilter16.o", "dfilter_bf16_inst.hip", []))
     units.append(("sconv16.o", "sconv_bf16_inst.hip", []))
+    units.append(("sfilter16.o", "sfilter_bf16_inst.hip", []))
     for bf in (0, 1):
         units.append(("sconv_%s.o" % ("bf16" if bf else "f32"), "sconv_inst.hip", ["-DOWT_INST_BF16=%d" % bf]))
     for bf in (0, 1):

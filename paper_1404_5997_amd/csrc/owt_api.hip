@@ -9,6 +9,7 @@
 #include "sconv.hpp"
 #include "sconv_bf16.hpp"
 #include "sfilter.hpp"
+#include "sfilter_bf16.hpp"
 
 namespace owt {
 
@@ -54,7 +55,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -177,6 +178,30 @@ static bool sfilter_geom(const Geom &g, SFilterGeom &sg)
     const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
     return sg.NB <= 4 * kSFilterACCS && lds <= 150 * 1024 && g.C <= 16 &&
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSFilterNT * kSFilterPNP && (long)sg.DZP * 16 <= (long)kSFilterNT * kSFilterDNP;
+}
+
+// Geometry of the bf16-MFMA small-channel strided filter-gradient kernel; false when it does not apply
+// (bf16 storage, K a multiple of 8, window starts and image rows that are multiples of 4 values, at
+// most 16 blocks of 32 columns, one band of rows + its dz values within 150 KB of LDS).
+static bool sfilter16_geom(const Geom &g, SFilter16Geom &sg)
+{
+    if (!g.bf16 || (g.sw * g.C) % 4 || (g.W * g.C) % 4 || g.K % 8 || g.C > 16) return false;
+    sg.SEG = g.S * g.C;
+    sg.LPAD = (4 - (g.pw * g.C) % 4) % 4;
+    sg.SLOTS = (sg.SEG + sg.LPAD + 3) & ~3;
+    const int a = g.pw * g.C + sg.LPAD + g.W * g.C, b = (g.Q - 1) * g.sw * g.C + sg.SLOTS;
+    sg.PITCH = ((a > b ? a : b) + 3) & ~3;
+    sg.ROWS = (kSFilter16TP - 1) * g.sh + g.R;
+    sg.NB = (g.R * sg.SLOTS + 31) / 32;
+    sg.MPIX = kSFilter16TP * g.Q;
+    sg.NGP = ((sg.MPIX + 31) / 32) * 2;            // groups of 16 pixels, an even number of them
+    sg.DZP = sg.NGP * 16;
+    sg.units_per_image = (g.P + kSFilter16TP - 1) / kSFilter16TP;
+    sg.units = g.N * sg.units_per_image;
+    const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 80) * 2 + (size_t)sg.DZP * 4;
+    return sg.NB <= (kSFilter16NT / 64) * kSFilter16CB && lds <= 150 * 1024 && sg.ROWS < 256 &&
+           (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSFilter16NT * kSFilter16PNP &&
+           sg.DZP <= (kSFilter16NT / 8) * kSFilter16DNP;
 }
 
 // Geometry of the small-channel strided forward kernel; false when it does not apply.
@@ -360,6 +385,29 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (force_split > 0) break;
         }
     }
+    SFilter16Geom sf16g;
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !getenv("OWT_NO_BF16_MFMA") && (g.sh > 1 || g.sw > 1) &&
+        sfilter16_geom(g, sf16g)) {
+        const long ktiles = cdiv(g.K, 64);
+        for (long target : {256L, 512L, 1024L}) {
+            long wgs = target / ktiles > 0 ? target / ktiles : 1;
+            if (force_split > 0) wgs = force_split;
+            if (wgs > sf16g.units) wgs = sf16g.units;
+            const long per = cdiv(sf16g.units, wgs), splits = cdiv(sf16g.units, per);
+            Launch l; memset(&l, 0, sizeof(l));
+            l.kind = KIND_SFILTER16; l.tile = 0; l.splits = (int)splits; l.steps = sf16g.units; l.steps_per_split = (int)per;
+            l.tiles_m = (int)ktiles; l.tiles_n = 1;
+            if (splits > 1) {
+                l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+            }
+            l.cost = model_cost(ktiles * splits, 8, 1, 64.0 * sf16g.NB * 32 * sf16g.DZP * per / 5.0, 1.0, splits, dm.M, dm.Ncols);
+            bool dup = false;
+            for (const Launch &o : out) dup |= o.kind == l.kind && o.splits == l.splits;
+            if (!dup) out.push_back(l);
+            if (force_split > 0) break;
+        }
+    }
     if (pass == OWT_PASS_BWD_FILTER && !no_direct) {
         for (int v = 0; v < 3; v++) {
             int taps, groups;
@@ -512,6 +560,11 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         p.splits = 1; p.partial = nullptr;
         e = bf ? owt_launch_sconv_bf16(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s)
                : owt_launch_sconv_f32(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s);
+    } else if (l.kind == KIND_SFILTER16) {
+        SFilter16Geom sg;
+        sfilter16_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        e = owt_launch_sfilter16(p, sg, l.tiles_m, s);
     } else if (l.kind == KIND_SFILTER) {
         SFilterGeom sg;
         sfilter_geom(g, sg);
@@ -553,6 +606,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     if (l.kind == KIND_SCONV)
         return snprintf(buf, n, "sconv %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConvTP, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConvNT);
+    if (l.kind == KIND_SFILTER16)
+        return snprintf(buf, n, "sfilter16 %s %s rows%d splitk%d grid%dx%d threads%ld", pn[pass], ds, kSFilter16TP, l.splits,
+                        l.tiles_m, l.splits, (long)l.tiles_m * l.splits * kSFilter16NT);
     if (l.kind == KIND_SFILTER)
         return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d threads%ld", pn[pass], ds, l.splits, l.tiles_m,
                         l.splits, (long)l.tiles_m * l.splits * kSFilterNT);

@@ -62,6 +62,10 @@ hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 struct SConv16Geom;
 hipError_t owt_launch_sconv16(const GemmParams &, const SConv16Geom &, int ktiles, int nwg, void *w2, hipStream_t);
 
+// bf16-MFMA small-channel strided filter-gradient kernel (sfilter_bf16_inst.hip).
+struct SFilter16Geom;
+hipError_t owt_launch_sfilter16(const GemmParams &, const SFilter16Geom &, int ktiles, hipStream_t);
+
 // Small-channel strided filter-gradient kernel (sfilter_inst.hip).
 struct SFilterGeom;
 hipError_t owt_launch_sfilter_f32(const GemmParams &, const SFilterGeom &, int ktiles, hipStream_t);

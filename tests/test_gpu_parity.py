@@ -211,6 +211,8 @@ def test_strided_small_channel_kernels(shape, split):
         if K % 4 == 0:       # bf16 storage takes the bf16-MFMA forward kernel; the line above ran it
             db = m.conv_desc(N, C, H, W, K, R, S, stride, pad, m.OWT_BF16, m.OWT_BIAS | m.OWT_RELU)
             assert m.owt_conv_plan_describe(db, m.OWT_PASS_FWD).startswith("sconv16"), m.owt_conv_plan_describe(db, 0)
+            if K % 8 == 0:   # ... and the bf16-MFMA filter-gradient kernel
+                assert m.owt_conv_plan_describe(db, m.OWT_PASS_BWD_FILTER).startswith("sfilter16"), m.owt_conv_plan_describe(db, 2)
             layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", seed=220 + split)
         os.environ["OWT_NO_BF16_MFMA"] = "1"                  # ... and this one the fp32-MFMA kernels on bf16 storage
         layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, seed=230 + split)
