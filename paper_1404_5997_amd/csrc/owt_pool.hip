@@ -82,6 +82,92 @@ __global__ void __launch_bounds__(256) maxpool_bwd_kernel(const T *__restrict__ 
     }
 }
 
+// bf16 storage with C a multiple of 8: eight channels per thread, 16-byte accesses (8 bytes of arg-max).
+__device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8])
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; j++) { f[2 * j] = __uint_as_float(w[j] << 16); f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u); }
+}
+
+__global__ void __launch_bounds__(256) maxpool_fwd_bf16x8_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ y,
+                                                                 unsigned char *__restrict__ am, int N, int H, int W, int C,
+                                                                 int win, int st, int P, int Q, FastDiv dCv, FastDiv dQ, FastDiv dP)
+{
+    const int Cv = C / 8;
+    const long total = (long)N * P * Q * Cv;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int pix = dCv.div((uint32_t)i), cv = (int)i - pix * Cv;
+        const int np = dQ.div(pix), q = pix - np * Q;
+        const int n = dP.div(np), p = np - n * P;
+        const int c = cv * 8;
+        float best[8]; uint32_t bits[8]; int bi[8];
+        const int base = ((n * H + p * st) * W + q * st) * C + c;
+        for (int r = 0; r < win; r++)
+            for (int s = 0; s < win; s++) {
+                const uint4 raw = *(const uint4 *)(x + base + (r * W + s) * C);
+                float v[8];
+                unpack8(raw, v);
+#pragma unroll
+                for (int j = 0; j < 8; j++)
+                    if ((r | s) == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = r * win + s; bits[j] = __float_as_uint(v[j]) >> 16; }
+            }
+        const size_t o = (size_t)pix * C + c;
+        uint4 out;                       // the maxima are input values: their bf16 bits are copied, not re-rounded
+        out.x = bits[0] | (bits[1] << 16); out.y = bits[2] | (bits[3] << 16);
+        out.z = bits[4] | (bits[5] << 16); out.w = bits[6] | (bits[7] << 16);
+        *(uint4 *)(y + o) = out;
+        uint2 a;
+        a.x = (uint32_t)bi[0] | ((uint32_t)bi[1] << 8) | ((uint32_t)bi[2] << 16) | ((uint32_t)bi[3] << 24);
+        a.y = (uint32_t)bi[4] | ((uint32_t)bi[5] << 8) | ((uint32_t)bi[6] << 16) | ((uint32_t)bi[7] << 24);
+        *(uint2 *)(am + o) = a;
+    }
+}
+
+__global__ void __launch_bounds__(256) maxpool_bwd_bf16x8_kernel(const uint16_t *__restrict__ dy, const unsigned char *__restrict__ am,
+                                                                 const uint16_t *__restrict__ yp, uint16_t *__restrict__ dx,
+                                                                 int N, int H, int W, int C, int win, int st, int P, int Q,
+                                                                 FastDiv dCv, FastDiv dW, FastDiv dH, FastDiv dst)
+{
+    const int Cv = C / 8;
+    const long total = (long)N * H * W * Cv;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int pix = dCv.div((uint32_t)i), cv = (int)i - pix * Cv;
+        const int nh = dW.div(pix), w = pix - nh * W;
+        const int n = dH.div(nh), h = nh - n * H;
+        const int c = cv * 8;
+        const int p_hi = min(P - 1, (int)dst.div(h)), q_hi = min(Q - 1, (int)dst.div(w));
+        const int p_lo = h >= win ? (int)dst.div(h - win + st) : 0;
+        const int q_lo = w >= win ? (int)dst.div(w - win + st) : 0;
+        float acc[8];
+#pragma unroll
+        for (int j = 0; j < 8; j++) acc[j] = 0.f;
+        for (int p = p_lo; p <= p_hi; p++)
+            for (int q = q_lo; q <= q_hi; q++) {
+                const int code = (h - p * st) * win + (w - q * st);
+                const int off = ((n * P + p) * Q + q) * C + c;
+                const uint2 a8 = *(const uint2 *)(am + off);
+                float gv[8];
+                unpack8(*(const uint4 *)(dy + off), gv);
+                if (yp) {   // fused ReLU backward: a window whose maximum is <= 0 passes nothing
+                    float yv[8];
+                    unpack8(*(const uint4 *)(yp + off), yv);
+#pragma unroll
+                    for (int j = 0; j < 8; j++) gv[j] = yv[j] > 0.f ? gv[j] : 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < 8; j++) {
+                    const uint32_t aw = j < 4 ? a8.x : a8.y;
+                    if ((int)((aw >> (8 * (j & 3))) & 255u) == code) acc[j] += gv[j];
+                }
+            }
+        uint4 out;
+        out.x = f32x2_to_bf16x2(acc[0], acc[1]); out.y = f32x2_to_bf16x2(acc[2], acc[3]);
+        out.z = f32x2_to_bf16x2(acc[4], acc[5]); out.w = f32x2_to_bf16x2(acc[6], acc[7]);
+        *(uint4 *)(dx + (size_t)pix * C + c) = out;
+    }
+}
+
 static owt_status check_pool(int N, int H, int W, int C, int win, int st, owt_dtype dt, int &P, int &Q)
 {
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0) return fail(OWT_EINVAL, "N,H,W,C must be positive");
@@ -110,13 +196,16 @@ owt_status owt_maxpool_fwd(int N, int H, int W, int C, int win, int stride, owt_
     if (st != OWT_OK) return st;
     if (!x || !y || !argmax) return fail(OWT_EINVAL, "x, y or argmax is NULL");
     if (!aligned16(x) || !aligned16(y) || !aligned16(argmax)) return fail(OWT_EINVAL, "misaligned pointer");
-    const int V = C % 4 == 0 ? 4 : 1;
+    const int V = (dtype == OWT_BF16 && C % 8 == 0) ? 8 : (C % 4 == 0 ? 4 : 1);
     FastDiv dCv, dQ, dP; dCv.set(C / V); dQ.set(Q); dP.set(P);
     const long total = (long)N * P * Q * (C / V);
     hipStream_t s = (hipStream_t)hip_stream;
+    if (V == 8)
+        hipLaunchKernelGGL(maxpool_fwd_bf16x8_kernel, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t *)x, (uint16_t *)y,
+                           argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP);
 #define OWT_POOL_F(T, VV) hipLaunchKernelGGL((maxpool_fwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \
         (const T *)x, (T *)y, argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP)
-    if (dtype == OWT_F32) { if (V == 4) OWT_POOL_F(float, 4); else OWT_POOL_F(float, 1); }
+    else if (dtype == OWT_F32) { if (V == 4) OWT_POOL_F(float, 4); else OWT_POOL_F(float, 1); }
     else { if (V == 4) OWT_POOL_F(bf16_t, 4); else OWT_POOL_F(bf16_t, 1); }
 #undef OWT_POOL_F
     const hipError_t e = hipGetLastError();
@@ -132,13 +221,16 @@ static owt_status pool_bwd(int N, int H, int W, int C, int win, int stride, owt_
     if (st != OWT_OK) return st;
     if (!dy || !dx || !argmax) return fail(OWT_EINVAL, "dy, dx or argmax is NULL");
     if (!aligned16(dy) || !aligned16(dx) || !aligned16(argmax)) return fail(OWT_EINVAL, "misaligned pointer");
-    const int V = C % 4 == 0 ? 4 : 1;
+    const int V = (dtype == OWT_BF16 && C % 8 == 0) ? 8 : (C % 4 == 0 ? 4 : 1);
     FastDiv dCv, dW, dH, dst; dCv.set(C / V); dW.set(W); dH.set(H); dst.set(stride);
     const long total = (long)N * H * W * (C / V);
     hipStream_t s = (hipStream_t)hip_stream;
+    if (V == 8)
+        hipLaunchKernelGGL(maxpool_bwd_bf16x8_kernel, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t *)dy, argmax,
+                           (const uint16_t *)yp, (uint16_t *)dx, N, H, W, C, win, stride, P, Q, dCv, dW, dH, dst);
 #define OWT_POOL_B(T, VV) hipLaunchKernelGGL((maxpool_bwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \
         (const T *)dy, argmax, (const T *)yp, (T *)dx, N, H, W, C, win, stride, P, Q, dCv, dW, dH, dst)
-    if (dtype == OWT_F32) { if (V == 4) OWT_POOL_B(float, 4); else OWT_POOL_B(float, 1); }
+    else if (dtype == OWT_F32) { if (V == 4) OWT_POOL_B(float, 4); else OWT_POOL_B(float, 1); }
     else { if (V == 4) OWT_POOL_B(bf16_t, 4); else OWT_POOL_B(bf16_t, 1); }
 #undef OWT_POOL_B
     const hipError_t e = hipGetLastError();
