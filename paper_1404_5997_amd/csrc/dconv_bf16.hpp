@@ -108,7 +108,9 @@ __global__ void __launch_bounds__(64 * WM * WN, 2) dconv_bf16_kernel(const GemmP
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
             const int n = n0 + line0 + i * RPP;
-            breg[i] = (n < p.Ncols && c < Cred) ? *(const uint4 *)(wsrc + ((size_t)n * RS + tap) * Cred + c) : zero4;
+            uint4 v = zero4;
+            if (n < p.Ncols && c < Cred) v = *(const uint4 *)(wsrc + ((size_t)n * RS + tap) * Cred + c);
+            breg[i] = v;
         }
     };
     auto store_b = [&](uint16_t *buf) {
