@@ -23,6 +23,8 @@ hipError_t owt_launch_dfilter16(int variant, const GemmParams &p, hipStream_t s)
                       kDFilter16Variants[1].prf>(p, s);
     case 2: return go<kDFilter16Variants[2].WK, kDFilter16Variants[2].WC, kDFilter16Variants[2].KB, kDFilter16Variants[2].tmax,
                       kDFilter16Variants[2].prf>(p, s);
+    case 3: return go<kDFilter16Variants[3].WK, kDFilter16Variants[3].WC, kDFilter16Variants[3].KB, kDFilter16Variants[3].tmax,
+                      kDFilter16Variants[3].prf>(p, s);
     default: return hipErrorInvalidValue;
     }
 }

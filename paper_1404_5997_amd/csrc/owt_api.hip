@@ -441,14 +441,14 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     if (pass == OWT_PASS_BWD_FILTER && !no_direct && !getenv("OWT_NO_BF16_MFMA")) {
-        for (int v = 0; v < 3; v++) {
+        for (int v = 0; v < 4; v++) {
             int taps, groups;
             if (force_tile >= 0 && force_tile != v) continue;
             if (!dfilter16_fits(g, v, taps, groups)) continue;
             const DFilter16Variant &dv = kDFilter16Variants[v];
             const long KT = 32 * dv.KB * dv.WK, CT = 32 * dv.WC;
             const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, kDFilter16BP);
-            for (long s0 : split_ladder(tm * ctl * groups, 1024 / (dv.WK * dv.WC))) {   // one wavefront per SIMD
+            for (long s0 : split_ladder(tm * ctl * groups, 256)) {            // one or two work-groups per CU
                 long s = s0;
                 if (force_split > 0) s = force_split < steps ? force_split : steps;
                 else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 1280)) break;
@@ -461,7 +461,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
                     l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                     l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
                 }
-                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, 4 / (dv.WK * dv.WC),
+                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, dv.WK * dv.WC <= 2 ? 2 : 1,
                                     (double)KT * CT * kDFilter16BP * taps * per / 5.0, 1.2,
                                     splits, dm.M, dm.Ncols);
                 bool dup = false;

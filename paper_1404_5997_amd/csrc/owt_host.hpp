@@ -54,7 +54,7 @@ hipError_t owt_launch_dfilter_bf16(int variant, const GemmParams &, hipStream_t)
 // bf16-MFMA direct filter-gradient kernel (dfilter_bf16_inst.hip): work-group tile 32*KB*WK filters x
 // 32*WC channels, 64-pixel chunks, tmax taps per work-group, prf panel rows.
 struct DFilter16Variant { int WK, WC, KB, tmax, prf; };
-constexpr DFilter16Variant kDFilter16Variants[3] = {{1, 4, 4, 3, 128}, {2, 2, 2, 5, 224}, {1, 2, 4, 3, 128}};
+constexpr DFilter16Variant kDFilter16Variants[4] = {{1, 4, 4, 3, 128}, {2, 2, 2, 5, 224}, {1, 2, 4, 3, 128}, {3, 2, 2, 5, 224}};
 constexpr int kDFilter16BP = 64;
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 

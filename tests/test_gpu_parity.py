@@ -170,7 +170,7 @@ def test_bf16_mfma_direct_kernel(tile, split):
             os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (0, 3), (1, 4), (2, 7)])
+@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (0, 3), (1, 4), (2, 7), (3, 5)])
 def test_bf16_mfma_filter_gradient_kernel(variant, split):
     # bf16 storage, stride 1, "same" padding, channels and filters multiples of 8: the filter gradient runs on
     # the bf16 MFMA, one filter row per work-group (3-tap variants 0 and 2, 5-tap variant 1)
@@ -178,7 +178,7 @@ def test_bf16_mfma_filter_gradient_kernel(variant, split):
     os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(variant), str(split)
     try:
         shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25))] \
-            if variant == 1 else \
+            if variant in (1, 3) else \
             [((4, 72, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
              ((3, 8, 6, 11, 8, 3, 3, 1), dict(relu=False, alpha=1.0 / 3, beta=1.0))]
         for (N, C, H, W, K, R, S, pad), kw in shapes:
