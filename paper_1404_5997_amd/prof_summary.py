@@ -34,6 +34,10 @@ def family(name):
         return "dfilter16 bwd_filter"
     if n.startswith("dfilter_kernel"):
         return "dfilter bwd_filter"
+    if n.startswith("sconv16_fwd_kernel"):
+        return "sconv16 fwd"
+    if n.startswith("sfilter16_kernel"):
+        return "sfilter16 bwd_filter"
     if n.startswith("sfilter_kernel"):
         return "sfilter bwd_filter"
     if n.startswith("sconv_fwd_kernel"):
@@ -45,7 +49,8 @@ def family(name):
 
 def is_step_start(name):
     n = short(name)
-    return n.startswith("sconv_pack_filters_kernel") or (n.startswith("igemm_kernel") and "FwdA" in n and "1, 1, 1, 1" in n)
+    return n.startswith("sconv_pack_filters_kernel") or n.startswith("sconv16_pack_filters_kernel") or \
+        (n.startswith("igemm_kernel") and "FwdA" in n and "1, 1, 1, 1" in n)
 
 
 def is_copy(name):
