@@ -125,7 +125,7 @@ static bool sconv16_geom(const Geom &g, SConv16Geom &sg)
     sg.units_per_image = (g.P + kSConv16TP - 1) / kSConv16TP;
     sg.units = g.N * sg.units_per_image;
     const size_t lds = ((size_t)64 * sg.WP + (size_t)2 * sg.ZROWS * sg.PITCH) * 2;     // filter bank + two bands
-    return sg.OCT >= 2 && sg.MPIX <= 256 && lds <= 150 * 1024 &&
+    return sg.OCT >= 2 && sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 &&
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)(kSConv16NT / 2) * kSConv16PNP;
 }
 
@@ -177,6 +177,7 @@ static bool sfilter_geom(const Geom &g, SFilterGeom &sg)
     sg.units = g.N * sg.units_per_image;
     const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
     return sg.NB <= 4 * kSFilterACCS && lds <= 150 * 1024 && g.C <= 16 &&
+           sg.ROWS < 256 && g.Q < 65536 &&
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSFilterNT * kSFilterPNP && (long)sg.DZP * 16 <= (long)kSFilterNT * kSFilterDNP;
 }
 
@@ -223,7 +224,7 @@ static bool sconv_geom(const Geom &g, SConvGeom &sg)
     const int zr = (kSConvTP - 1) * g.sh + (sg.KSLOTS - 1) / sg.SLOTS + 1;
     sg.ZROWS = zr > sg.ROWS + 1 ? zr : sg.ROWS + 1;
     const size_t lds = ((size_t)2 * 64 * (kSConvBK + 4) + (size_t)sg.ZROWS * sg.PITCH) * 4;
-    return sg.MPIX <= 256 && lds <= 150 * 1024 && (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
+    return sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 && (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
 }
 
 struct Launch {

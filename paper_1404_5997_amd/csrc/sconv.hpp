@@ -66,25 +66,30 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     const int bq = tid % BQ, bl0 = tid / BQ;                    // filter-slice loader: quad, filter line
     constexpr int BLPP = NT / BQ;                               // lines per pass (51 for 512 threads)
 
+    // piece `it` of this thread is (row, float4 f4) of the band, the same for every band: the divisions
+    // happen once (row | f4 << 8, or -1 past the band)
+    int prf[PNP];
+#pragma unroll
+    for (int it = 0; it < PNP; it++) {
+        const int i = tid + it * NT;
+        const int row = i / row_f4, f4 = i - row * row_f4;
+        prf[it] = i < panel_f4 ? (row | (f4 << 8)) : -1;
+    }
     auto load_band = [&](int u) {
         const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
         const int h0 = p0 * g.sh - g.ph;
 #pragma unroll
         for (int it = 0; it < PNP; it++) {
-            const int i = tid + it * NT;
-            const int row = i / row_f4, f4 = i - row * row_f4, h = h0 + row;
+            const int row = prf[it] & 255, f4 = prf[it] >> 8, h = h0 + row;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < panel_f4 && (unsigned)h < (unsigned)g.H) v = load4(xsrc, ((n * g.H + h) * g.W) * g.C + f4 * 4);
+            if (prf[it] >= 0 && (unsigned)h < (unsigned)g.H) v = load4(xsrc, ((n * g.H + h) * g.W) * g.C + f4 * 4);
             preg[it] = v;
         }
     };
     auto store_band = [&]() {
 #pragma unroll
-        for (int it = 0; it < PNP; it++) {
-            const int i = tid + it * NT;
-            const int row = i / row_f4, f4 = i - row * row_f4;
-            if (i < panel_f4) *(float4 *)(panel + row * sg.PITCH + img_off + f4 * 4) = preg[it];
-        }
+        for (int it = 0; it < PNP; it++)
+            if (prf[it] >= 0) *(float4 *)(panel + (prf[it] & 255) * sg.PITCH + img_off + (prf[it] >> 8) * 4) = preg[it];
     };
     auto load_b = [&](int step) {
 #pragma unroll

@@ -72,24 +72,37 @@ __global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, cons
 
     // global -> registers for one unit (two output rows of one image), registers -> LDS
     float4 preg[PNP], dreg[DNP];
+    // the pieces a thread stages are the same (row, float4) / (pixel, filter quad) for every unit:
+    // the divisions happen once (row | f4 << 8 and pixel-in-row | output row << 16, or -1 when unused)
+    int prf[PNP], dpq[DNP];
+#pragma unroll
+    for (int it = 0; it < PNP; it++) {
+        const int i = tid + it * NT;
+        const int row = i / row_f4, f4 = i - row * row_f4;
+        prf[it] = i < panel_f4 ? (row | (f4 << 8)) : -1;
+    }
+#pragma unroll
+    for (int it = 0; it < DNP; it++) {
+        const int i = tid + it * NT;
+        const int pix = i / (KB / 4), pl = pix / g.Q, q = pix - pl * g.Q;
+        dpq[it] = (i < dz_f4 && pl < TP) ? (q | (pl << 16)) : -1;
+    }
+    const int dkq = tid % (KB / 4);                                  // NT is a multiple of KB/4: the same quad every time
     auto load_unit = [&](int u) {
         const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
         const int h0 = p0 * g.sh - g.ph;
 #pragma unroll
         for (int it = 0; it < PNP; it++) {
-            const int i = tid + it * NT;
-            const int row = i / row_f4, f4 = i - row * row_f4, h = h0 + row;
+            const int row = prf[it] & 255, f4 = prf[it] >> 8, h = h0 + row;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < panel_f4 && (unsigned)h < (unsigned)g.H) v = load4(xsrc, ((n * g.H + h) * g.W) * g.C + f4 * 4);
+            if (prf[it] >= 0 && (unsigned)h < (unsigned)g.H) v = load4(xsrc, ((n * g.H + h) * g.W) * g.C + f4 * 4);
             preg[it] = v;
         }
 #pragma unroll
         for (int it = 0; it < DNP; it++) {
-            const int i = tid + it * NT;
-            const int pix = i / (KB / 4), kq = i - pix * (KB / 4);
-            const int pl = pix / g.Q, q = pix - pl * g.Q, pp = p0 + pl, k = k0 + kq * 4;
+            const int q = dpq[it] & 0xffff, pp = p0 + (dpq[it] >> 16), k = k0 + dkq * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (i < dz_f4 && pl < TP && pp < g.P && k < g.K) {
+            if (dpq[it] >= 0 && pp < g.P && k < g.K) {
                 const int off = ((n * g.P + pp) * g.Q + q) * g.K + k;
                 v = load4(dzsrc, off);
                 if (mask) {
@@ -103,17 +116,13 @@ __global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, cons
     };
     auto store_unit = [&]() {
 #pragma unroll
-        for (int it = 0; it < PNP; it++) {
-            const int i = tid + it * NT;
-            const int row = i / row_f4, f4 = i - row * row_f4;
-            if (i < panel_f4) *(float4 *)(panel + row * sg.PITCH + img_off + f4 * 4) = preg[it];
-        }
+        for (int it = 0; it < PNP; it++)
+            if (prf[it] >= 0) *(float4 *)(panel + (prf[it] & 255) * sg.PITCH + img_off + (prf[it] >> 8) * 4) = preg[it];
 #pragma unroll
         for (int it = 0; it < DNP; it++) {
             const int i = tid + it * NT;
-            const int pix = i / (KB / 4), kq = i - pix * (KB / 4);
             if (i < dz_f4) {
-                *(float4 *)(dzs + pix * DZPITCH + kq * 4) = dreg[it];
+                *(float4 *)(dzs + (i / (KB / 4)) * DZPITCH + dkq * 4) = dreg[it];
                 if (do_db) { dbacc.x += dreg[it].x; dbacc.y += dreg[it].y; dbacc.z += dreg[it].z; dbacc.w += dreg[it].w; }
             }
         }
