@@ -224,7 +224,8 @@ static bool sconv_geom(const Geom &g, SConvGeom &sg)
     const int zr = (kSConvTP - 1) * g.sh + (sg.KSLOTS - 1) / sg.SLOTS + 1;
     sg.ZROWS = zr > sg.ROWS + 1 ? zr : sg.ROWS + 1;
     const size_t lds = ((size_t)2 * 64 * (kSConvBK + 4) + (size_t)sg.ZROWS * sg.PITCH) * 4;
-    return sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 && (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
+    return sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 && sg.SLOTS >= 8 &&
+           (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
 }
 
 struct Launch {

@@ -123,6 +123,10 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
         for (int i = 0; i < 2; i++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
+        // quad index step*BQ + 2*cc + lh of this lane, as (filter row qr, quad qj of that row): advanced by
+        // two quads per group instead of dividing every time (BQ is even, a row has at least two quads)
+        int qr = 0, qj = lh;
+        if (qj >= qpr) { qj -= qpr; qr++; }
         for (int step = 0; step < sg.KSTEPS; step++) {
             const bool last = step + 1 == sg.KSTEPS;
             if (!last || more_u) load_b(last ? 0 : step + 1);
@@ -130,9 +134,9 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
             const float *Bc = Bs + cur * KB * WP;
 #pragma unroll
             for (int cc = 0; cc < BQ / 2; cc++) {
-                const int quad = step * BQ + 2 * cc + lh;
-                const int r = quad / qpr, jq = quad - r * qpr;
-                const float4 a = *(const float4 *)(panel + abase + (mvalid ? r * sg.PITCH + jq * 4 : 0));
+                const float4 a = *(const float4 *)(panel + abase + (mvalid ? qr * sg.PITCH + qj * 4 : 0));
+                qj += 2;
+                if (qj >= qpr) { qj -= qpr; qr++; }
                 const float4 b0 = *(const float4 *)(Bc + li * WP + (2 * cc + lh) * 4);
                 const float4 b1 = *(const float4 *)(Bc + (32 + li) * WP + (2 * cc + lh) * 4);
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b0.x, acc[0], 0, 0, 0);
