@@ -850,23 +850,25 @@ owt_status owt_conv_autotune(const owt_conv_desc *d, int pass, const void *x, co
     enumerate(g, pass, dm, pass == OWT_PASS_BWD_FILTER, c);
     for (const Launch &l : c) OWT_TRY(check_ws(l, ws, ws_bytes));
     hipStream_t s = (hipStream_t)hip_stream;
+    if (c.empty()) return fail(OWT_EUNSUPPORTED, "no kernel variant for this geometry");
     hipEvent_t e0, e1;
-    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)
-        return fail(OWT_ELAUNCH, "hipEventCreate failed");
+    if (hipEventCreate(&e0) != hipSuccess) return fail(OWT_ELAUNCH, "hipEventCreate failed");
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(OWT_ELAUNCH, "hipEventCreate failed"); }
     int best = -1; float best_ms = 0.f;
     owt_status st = OWT_OK;
     for (size_t i = 0; i < c.size() && st == OWT_OK; i++) {
         st = launch(g, pass, d->dtype, dm, p, c[i], ws, s);                       // warm-up
         if (st != OWT_OK) break;
-        hipEventRecord(e0, s);
+        bool ok = hipEventRecord(e0, s) == hipSuccess;
         for (int r = 0; r < 3 && st == OWT_OK; r++) st = launch(g, pass, d->dtype, dm, p, c[i], ws, s);
-        hipEventRecord(e1, s);
-        if (hipEventSynchronize(e1) != hipSuccess) { st = fail(OWT_ELAUNCH, "hipEventSynchronize failed"); break; }
+        if (st != OWT_OK) break;
         float ms = 0.f;
-        hipEventElapsedTime(&ms, e0, e1);
+        ok = ok && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+             hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+        if (!ok) { st = fail(OWT_ELAUNCH, "timing a kernel variant failed: %s", hipGetErrorString(hipGetLastError())); break; }
         if (best < 0 || ms < best_ms) { best = (int)i; best_ms = ms; }
     }
-    hipEventDestroy(e0); hipEventDestroy(e1);
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
     if (st != OWT_OK) return st;
     std::lock_guard<std::mutex> lk(g_tuned_mutex);
     g_tuned[plan_key(g, pass, d->dtype)] = c[best];
