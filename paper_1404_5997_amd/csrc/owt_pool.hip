@@ -168,6 +168,106 @@ __global__ void __launch_bounds__(256) maxpool_bwd_bf16x8_kernel(const uint16_t 
     }
 }
 
+// Backward pass specialised for the 3x3 window, stride 2 pooling of the Section 5 model.  A thread
+// owns a 2x2 block of dx (rows 2a, 2a+1, columns 2b, 2b+1) and V channels: only the four windows
+// (a-1..a, b-1..b) can route a gradient into it, so every window is read once per block instead of
+// once per input element (2.25x less cache traffic than the gather above).  Window (p, q) with
+// arg-max code 3r+s sends its gradient to input (2p+r, 2q+s).
+template <class T, int V> struct PoolVec;
+template <> struct PoolVec<float, 4> {
+    static __device__ __forceinline__ void load(const float *p, size_t off, float (&f)[4])
+    {
+        const float4 v = *(const float4 *)(p + off);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    static __device__ __forceinline__ void store(float *p, size_t off, const float (&f)[4])
+    {
+        *(float4 *)(p + off) = make_float4(f[0], f[1], f[2], f[3]);
+    }
+    static __device__ __forceinline__ void codes(const unsigned char *am, size_t off, int (&c)[4])
+    {
+        const uint32_t a = *(const uint32_t *)(am + off);
+        c[0] = a & 255u; c[1] = (a >> 8) & 255u; c[2] = (a >> 16) & 255u; c[3] = a >> 24;
+    }
+};
+template <> struct PoolVec<bf16_t, 8> {
+    static __device__ __forceinline__ void load(const bf16_t *p, size_t off, float (&f)[8])
+    {
+        unpack8(*(const uint4 *)((const uint16_t *)p + off), f);
+    }
+    static __device__ __forceinline__ void store(bf16_t *p, size_t off, const float (&f)[8])
+    {
+        uint4 o;
+        o.x = f32x2_to_bf16x2(f[0], f[1]); o.y = f32x2_to_bf16x2(f[2], f[3]);
+        o.z = f32x2_to_bf16x2(f[4], f[5]); o.w = f32x2_to_bf16x2(f[6], f[7]);
+        *(uint4 *)((uint16_t *)p + off) = o;
+    }
+    static __device__ __forceinline__ void codes(const unsigned char *am, size_t off, int (&c)[8])
+    {
+        const uint2 a = *(const uint2 *)(am + off);
+#pragma unroll
+        for (int j = 0; j < 8; j++) c[j] = ((j < 4 ? a.x : a.y) >> (8 * (j & 3))) & 255u;
+    }
+};
+
+template <class T, int V>
+__global__ void __launch_bounds__(256) maxpool_bwd_w3s2_kernel(const T *__restrict__ dy, const unsigned char *__restrict__ am,
+                                                               const T *__restrict__ yp, T *__restrict__ dx, int N, int H, int W,
+                                                               int C, int P, int Q, FastDiv dCv, FastDiv dWb, FastDiv dHb)
+{
+    const int Cv = C / V, Hb = (H + 1) / 2, Wb = (W + 1) / 2;
+    const long total = (long)N * Hb * Wb * Cv;
+    for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
+        const int blk = dCv.div((uint32_t)i), cv = (int)i - blk * Cv;
+        const int na = dWb.div(blk), b = blk - na * Wb;
+        const int n = dHb.div(na), a = na - n * Hb;
+        const int c = cv * V;
+        float acc[2][2][V];
+#pragma unroll
+        for (int hr = 0; hr < 2; hr++)
+#pragma unroll
+            for (int wc = 0; wc < 2; wc++)
+#pragma unroll
+                for (int j = 0; j < V; j++) acc[hr][wc][j] = 0.f;
+#pragma unroll
+        for (int dp = 0; dp < 2; dp++)
+#pragma unroll
+            for (int dq = 0; dq < 2; dq++) {
+                const int p = a - 1 + dp, q = b - 1 + dq;
+                if ((unsigned)p >= (unsigned)P || (unsigned)q >= (unsigned)Q) continue;
+                const size_t off = ((size_t)(n * P + p) * Q + q) * C + c;
+                int code[V];
+                float g[V];
+                PoolVec<T, V>::codes(am, off, code);
+                PoolVec<T, V>::load(dy, off, g);
+                if (yp) {   // fused ReLU backward: a window whose maximum is <= 0 passes nothing
+                    float y[V];
+                    PoolVec<T, V>::load(yp, off, y);
+#pragma unroll
+                    for (int j = 0; j < V; j++) g[j] = y[j] > 0.f ? g[j] : 0.f;
+                }
+                // window row r lands on block row (dp == 1 ? r : r - 2), likewise for columns
+#pragma unroll
+                for (int hr = 0; hr < 2; hr++)
+#pragma unroll
+                    for (int wc = 0; wc < 2; wc++) {
+                        const int r = dp ? hr : hr + 2, sc = dq ? wc : wc + 2;
+                        if (r > 2 || sc > 2) continue;           // compile-time: that element is outside this window
+#pragma unroll
+                        for (int j = 0; j < V; j++)
+                            if (code[j] == 3 * r + sc) acc[hr][wc][j] += g[j];
+                    }
+            }
+#pragma unroll
+        for (int hr = 0; hr < 2; hr++)
+#pragma unroll
+            for (int wc = 0; wc < 2; wc++) {
+                const int h = 2 * a + hr, w = 2 * b + wc;
+                if (h < H && w < W) PoolVec<T, V>::store(dx, ((size_t)(n * H + h) * W + w) * C + c, acc[hr][wc]);
+            }
+    }
+}
+
 static owt_status check_pool(int N, int H, int W, int C, int win, int st, owt_dtype dt, int &P, int &Q)
 {
     if (N <= 0 || H <= 0 || W <= 0 || C <= 0) return fail(OWT_EINVAL, "N,H,W,C must be positive");
@@ -225,7 +325,16 @@ static owt_status pool_bwd(int N, int H, int W, int C, int win, int stride, owt_
     FastDiv dCv, dW, dH, dst; dCv.set(C / V); dW.set(W); dH.set(H); dst.set(stride);
     const long total = (long)N * H * W * (C / V);
     hipStream_t s = (hipStream_t)hip_stream;
-    if (V == 8)
+    if (win == 3 && stride == 2 && ((dtype == OWT_F32 && V == 4) || (dtype == OWT_BF16 && V == 8))) {
+        FastDiv dWb, dHb; dWb.set((W + 1) / 2); dHb.set((H + 1) / 2);
+        const long blocks = (long)N * ((H + 1) / 2) * ((W + 1) / 2) * (C / V);
+        if (dtype == OWT_F32)
+            hipLaunchKernelGGL((maxpool_bwd_w3s2_kernel<float, 4>), dim3(grid_for(blocks)), dim3(256), 0, s, (const float *)dy,
+                               argmax, (const float *)yp, (float *)dx, N, H, W, C, P, Q, dCv, dWb, dHb);
+        else
+            hipLaunchKernelGGL((maxpool_bwd_w3s2_kernel<bf16_t, 8>), dim3(grid_for(blocks)), dim3(256), 0, s, (const bf16_t *)dy,
+                               argmax, (const bf16_t *)yp, (bf16_t *)dx, N, H, W, C, P, Q, dCv, dWb, dHb);
+    } else if (V == 8)
         hipLaunchKernelGGL(maxpool_bwd_bf16x8_kernel, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t *)dy, argmax,
                            (const uint16_t *)yp, (uint16_t *)dx, N, H, W, C, win, stride, P, Q, dCv, dW, dH, dst);
 #define OWT_POOL_B(T, VV) hipLaunchKernelGGL((maxpool_bwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \

@@ -349,7 +349,7 @@ def test_fc_shard_bwd_without_dx_or_dbias():
 @pytest.mark.parametrize("N,H,W,C,win,st,dt", [
     (3, 13, 13, 8, 3, 2, "f32"), (2, 55, 55, 64, 3, 2, "f32"), (2, 9, 12, 5, 3, 2, "f32"),
     (2, 10, 7, 4, 2, 2, "f32"), (1, 8, 8, 3, 4, 1, "f32"), (2, 27, 27, 192, 3, 2, "bf16"), (2, 7, 7, 3, 3, 2, "bf16"),
-    (2, 10, 7, 12, 2, 2, "bf16"), (1, 9, 9, 8, 4, 1, "bf16"),
+    (2, 10, 7, 12, 2, 2, "bf16"), (1, 9, 9, 8, 4, 1, "bf16"), (2, 12, 10, 8, 3, 2, "f32"), (2, 12, 10, 16, 3, 2, "bf16"), (1, 3, 3, 4, 3, 2, "f32"),
 ])
 def test_maxpool_parity(N, H, W, C, win, st, dt):
     m = owt()
