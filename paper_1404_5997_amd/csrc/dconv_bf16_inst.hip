@@ -1,6 +1,6 @@
 // Instantiations of the bf16-MFMA stride-1 kernel for one pass.
 // Built twice: -DOWT_INST_PASS={0,1}.
-#include "dconv_bf16.hpp"
+#include "dconv_bf16p.hpp"
 #include "owt_host.hpp"
 
 #ifndef OWT_INST_PASS
@@ -27,6 +27,16 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
     return e;
 }
 
+template <int PR>
+static hipError_t go_pipelined(const GemmParams &p, hipStream_t s)
+{
+    const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
+    hipLaunchKernelGGL((dconv16p_kernel<OE, kBwd, PR>), grid, dim3(256), 0, s, p);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<OE>(p, s);
+    return e;
+}
+
 static hipError_t dispatch(int tile, int pr, const GemmParams &p, hipStream_t s)
 {
     if (tile == TILE_128x128) {
@@ -38,6 +48,9 @@ static hipError_t dispatch(int tile, int pr, const GemmParams &p, hipStream_t s)
     } else if (tile == TILE_256x64) {
         if (pr <= 288) return go<4, 1, 288>(p, s);
         if (pr <= 384) return go<4, 1, 384>(p, s);
+    } else if (tile == TILE_512x64 && p.Ncols % 4 == 0) {
+        if (pr <= 544) return go_pipelined<544>(p, s);
+        if (pr <= 624) return go_pipelined<624>(p, s);
     }
     return hipErrorInvalidValue;
 }

@@ -25,7 +25,7 @@ owt_status fail(owt_status st, const char *fmt, ...)
 }
 void clear_error() { g_err[0] = 0; }
 
-const TileInfo kTiles[NUM_TILES + 3] = {
+const TileInfo kTiles[NUM_TILES + 4] = {
     {TILE_128x128, 2, 2, 32, 1.00f, 128},
     {TILE_128x64, 2, 1, 16, 0.90f, 128},
     {TILE_64x128, 1, 2, 16, 0.90f, 64},
@@ -33,6 +33,7 @@ const TileInfo kTiles[NUM_TILES + 3] = {
     {TILE_256x64, 4, 1, 32, 1.00f, 256},
     {TILE_128x64H, 4, 1, 32, 1.00f, 128},
     {TILE_128x128H, 4, 2, 32, 1.00f, 128},
+    {TILE_512x64, 4, 1, 32, 1.00f, 512},
 };
 
 static inline long cdiv(long a, long b) { return (a + b - 1) / b; }
@@ -308,15 +309,17 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (force_split > 0) break;
         }
     }
-    if (g.bf16 && cred % 8 == 0 && !getenv("OWT_NO_BF16_MFMA")) {      // same tiles on the bf16 MFMA, 64-channel chunks
-        for (int t : {TILE_128x128, TILE_128x64, TILE_256x64}) {
+    if (g.bf16 && cred % 8 == 0 && !getenv("OWT_NO_BF16_MFMA")) {      // the bf16 MFMA: 64-channel chunks, or 32 in the 512x64 tile
+        for (int t : {TILE_128x128, TILE_128x64, TILE_256x64, TILE_512x64}) {
             if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
             const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
             int pr;
-            if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
+            if (t == TILE_512x64) { if (rows < 0 || rows > 624 || dm.Ncols % 4) continue; pr = rows <= 544 ? 544 : 624; }
+            else if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
             else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : 256; }
-            const long chunks = cdiv(cred, 64);
-            const double macs = (double)BM * 64 * kTiles[t].WN * 64 * g.R * g.S / 6.0;   // ~6x the fp32 MFMA rate
+            const long bk = t == TILE_512x64 ? 32 : 64, chunks = cdiv(cred, bk);
+            // ~6x the fp32 MFMA rate; the pipelined tile keeps the matrix unit about 1.5x busier
+            const double macs = (double)BM * 64 * kTiles[t].WN * bk * g.R * g.S / (t == TILE_512x64 ? 9.0 : 6.0);
             const size_t n0 = out.size();
             for (long s : kSplits) {
                 if (s > 1 && (chunks / s < 1 || s > 8 || s > chunks)) break;
@@ -629,8 +632,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     const TileInfo &ti = kTiles[l.tile];
     const long threads = (long)l.tiles_m * l.tiles_n * l.splits * 64 * ti.WM * ti.WN;
     if (l.kind == KIND_DIRECT16)
-        return snprintf(buf, n, "dconv16 %s %s tile%dx%dx64 waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
-                        ti.BM, 64 * ti.WN, ti.WM, ti.WN, l.pr, l.splits, l.tiles_m * l.tiles_n, l.splits, threads);
+        return snprintf(buf, n, "dconv16 %s %s tile%dx%dx%d waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
+                        ti.BM, 64 * ti.WN, l.tile == TILE_512x64 ? 32 : 64, ti.WM, ti.WN, l.pr, l.splits,
+                        l.tiles_m * l.tiles_n, l.splits, threads);
     if (l.kind == KIND_DIRECT)
         return snprintf(buf, n, "dconv %s %s tile%dx%dx%d waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
                         ti.BM, 64 * ti.WN, l.tile == TILE_128x64 ? 16 : 32, ti.WM, ti.WN, l.pr, l.splits,
@@ -753,7 +757,7 @@ int owt_selftest_host(void)
                 const long parts = (l.kind == KIND_SCONV || l.kind == KIND_SCONV16) ? l.tiles_n : l.splits;   // who shares the steps
                 if (l.splits < 1 || parts * l.steps_per_split < l.steps ||
                     (parts - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
-                    ((l.kind == KIND_DIRECT || l.kind == KIND_DIRECT16) && (l.pr > 384 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {
+                    ((l.kind == KIND_DIRECT || l.kind == KIND_DIRECT16) && (l.pr > 624 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {
                     fail(OWT_EINVAL, "bad candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 4;
                 }
             }

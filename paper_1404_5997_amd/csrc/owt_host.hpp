@@ -18,9 +18,10 @@ inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 // Tile shapes the implicit-GEMM kernel is instantiated for.
 struct TileInfo { int id, WM, WN, BK; float eff; int BM; };
 // ids 0..3 exist for the gather kernel; the stride-1 direct kernel has 128x128, 128x64, 256x64 and
-// 128x64H (four wavefronts of 32x64 instead of two of 64x64: twice the wavefronts for small layers)
-enum { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x128 = 2, TILE_64x64 = 3, NUM_TILES = 4, TILE_256x64 = 4, TILE_128x64H = 5, TILE_128x128H = 6 };
-extern const TileInfo kTiles[NUM_TILES + 3];
+// 128x64H (four wavefronts of 32x64 instead of two of 64x64: twice the wavefronts for small layers);
+// 512x64 (four wavefronts of 128x64, 32-channel chunks) is the pipelined bf16-MFMA kernel only
+enum { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x128 = 2, TILE_64x64 = 3, NUM_TILES = 4, TILE_256x64 = 4, TILE_128x64H = 5, TILE_128x128H = 6, TILE_512x64 = 7 };
+extern const TileInfo kTiles[NUM_TILES + 4];
 
 bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw);
 
@@ -39,7 +40,7 @@ hipError_t owt_launch_dconv_fwd_bf16(int tile, int pr, const GemmParams &, hipSt
 hipError_t owt_launch_dconv_data_f32(int tile, int pr, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dconv_data_bf16(int tile, int pr, const GemmParams &, hipStream_t);
 
-// Panel-resident stride-1 kernel on the bf16 MFMA (dconv_bf16_inst.hip).  The backward-data
+// Panel-resident stride-1 kernels on the bf16 MFMA (dconv_bf16_inst.hip, dconv_bf16p.hpp for the 512x64 tile).  The backward-data
 // launcher first writes the flipped, transposed filters to the front of `ws`.
 hipError_t owt_launch_dconv16_fwd(int tile, int pr, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dconv16_data(int tile, int pr, const GemmParams &, void *ws, hipStream_t);

@@ -149,7 +149,7 @@ def test_every_tile_shape_and_split_k(tile, split, direct):
             os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2)])
+@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2), (7, 1), (7, 2), (7, 3)])
 def test_bf16_mfma_direct_kernel(tile, split):
     # bf16 storage, stride 1, reduction channels a multiple of 8: forward and backward-data run on the
     # bf16 MFMA kernel (64-channel chunks; backward-data reads re-laid-out filters from the workspace)
