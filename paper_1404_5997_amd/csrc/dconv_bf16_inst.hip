@@ -48,7 +48,7 @@ static hipError_t dispatch(int tile, int pr, const GemmParams &p, hipStream_t s)
     } else if (tile == TILE_256x64) {
         if (pr <= 288) return go<4, 1, 288>(p, s);
         if (pr <= 384) return go<4, 1, 384>(p, s);
-    } else if (tile == TILE_512x64 && p.Ncols % 4 == 0) {
+    } else if (tile == TILE_512x64 && p.Ncols % 4 == 0 && p.Cred % 32 == 0 && p.g.R * p.g.S >= 2 && p.g.R * p.g.S <= 32) {
         if (pr <= 544) return go_pipelined<544>(p, s);
         if (pr <= 624) return go_pipelined<624>(p, s);
     }

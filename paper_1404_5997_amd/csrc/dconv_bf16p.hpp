@@ -9,11 +9,19 @@
 //     phase every pixel fragment is re-read for the NEXT phase right after its last use, and the
 //     filter fragments of the next phase are read at the start of the phase, so a fragment is
 //     requested about six MFMAs before it is needed;
-//   * the one barrier per tap sits between the two phases: the filter slice of tap t+1 is stored
-//     before it, the first fragments of tap t+1 are read after it, the global load of the slice of
-//     tap t+2 is issued after it and has a whole tap to arrive.
+//   * the filter slice of a tap goes from global memory straight into LDS (global_load_lds, 16 bytes
+//     per lane, a wavefront's 64 pieces land back to back): no staging registers, no LDS store.  The
+//     slice is therefore unpadded (64-byte lines) and the 16-byte piece c of line n sits at position
+//     c ^ ((n >> 2) & 3), which keeps the fragment reads free of bank conflicts.  The two slice
+//     buffers and the panel are separate __shared__ arrays and the tap loop is unrolled by two: the
+//     compiler then knows which array a transfer in flight writes and does not make the fragment
+//     reads of the other arrays wait for it;
+//   * the one barrier per tap sits between the two phases: the transfer of the slice of tap t+1 is
+//     waited for before it, the first fragments of tap t+1 are read after it, and the transfer of
+//     the slice of tap t+2 is issued after it, into the buffer whose last reads ended before it.
 // The accumulators hold the TRANSPOSED tile (filters along MFMA rows, pixels along columns): a lane
 // then owns four consecutive filters of one pixel and stores 8 bytes at a time.
+// Needs the reduction channels to be a multiple of 32 and at most 32 filter taps (host-checked).
 #pragma once
 #include "dconv_bf16.hpp"
 
@@ -22,13 +30,14 @@ namespace owt {
 template <class Epi, bool BWD, int PR>
 __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
 {
-    constexpr int BK = 32, NT = 256, MB = 4, BM = 512, BN = 64, PITCH = BK + 8;   // bf16 elements: 80-byte rows
+    constexpr int BK = 32, NT = 256, MB = 4, BM = 512, BN = 64, PITCH = BK + 8;   // panel rows: 80 bytes
     constexpr int OCTS = BK / 8, RPP = NT / OCTS, PNP = (PR + RPP - 1) / RPP;
-    constexpr int BT = BN * PITCH;
+    constexpr int BT = BN * BK;                                  // bf16 elements per filter-slice buffer
     static_assert(BN * OCTS == NT, "one 16-byte piece of the filter slice per thread");
 
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * BT + (PR + 1) * PITCH];
-    uint16_t *panel = lds + 2 * BT;
+    __shared__ __attribute__((aligned(16))) uint16_t slice0[BT];
+    __shared__ __attribute__((aligned(16))) uint16_t slice1[BT];
+    __shared__ __attribute__((aligned(16))) uint16_t panel[(PR + 1) * PITCH];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int li = lane & 31, lh = lane >> 5;
@@ -55,26 +64,37 @@ __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
     const int ps = pin(m0, th, tw);
     const int nrows = pin(min(m0 + BM, p.M) - 1, th, tw) + (R - 1) * Wi + S - ps;   // <= PR (host-checked)
 
-    int hh[MB], ww[MB], prow[MB];
+    // per 32-pixel block of this lane: element offset of its panel row at tap (0,0), and one bit per
+    // tap telling whether the tap falls inside the image (else the row of zeros is read)
+    constexpr int ZOFF = PR * PITCH;
+    int poff[MB];
+    unsigned inside[MB];
 #pragma unroll
     for (int bm = 0; bm < MB; bm++) {
         const int m = m0 + wm0 + bm * 32 + li;
-        if (m < p.M) prow[bm] = pin(m, hh[bm], ww[bm]) - ps;
-        else { hh[bm] = kInvalidLo; ww[bm] = 0; prow[bm] = 0; }
+        poff[bm] = lh * 8;
+        inside[bm] = 0u;
+        if (m < p.M) {
+            int hh, ww;
+            poff[bm] += (pin(m, hh, ww) - ps) * PITCH;
+            for (int r = 0, tap = 0; r < R; r++)
+                for (int s = 0; s < S; s++, tap++)
+                    if ((unsigned)(hh + r) < (unsigned)Hi && (unsigned)(ww + s) < (unsigned)Wi) inside[bm] |= 1u << tap;
+        }
     }
 
     const uint16_t *in = (const uint16_t *)p.a, *wsrc = (const uint16_t *)p.b, *mask = (const uint16_t *)p.mask;
     const int oct = tid % OCTS, line0 = tid / OCTS;
-    uint4 preg[PNP], breg;
+    uint4 preg[PNP];
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
 
-    auto load_panel = [&](int ch) {
+    auto load_panel = [&](int ch) __attribute__((always_inline)) {
         const int c = ch * BK + oct * 8;
 #pragma unroll
         for (int i = 0; i < PNP; i++) {
             const int row = line0 + i * RPP, pix = ps + row;
             uint4 v = zero4;
-            if (row < nrows && (unsigned)pix < (unsigned)npix_in && c < Cred) {
+            if (row < nrows && (unsigned)pix < (unsigned)npix_in) {
                 const size_t off = (size_t)pix * Cred + c;
                 v = *(const uint4 *)(in + off);
                 if (BWD && mask) {
@@ -86,41 +106,52 @@ __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
             preg[i] = v;
         }
     };
-    auto store_panel = [&]() {
+    auto store_panel = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < PNP; i++) {
             const int row = line0 + i * RPP;
             if (row < PR) *(uint4 *)(panel + row * PITCH + oct * 8) = preg[i];
         }
     };
-    // line = output column (a filter in forward, an input channel in backward-data), oct along the reduction
-    const bool bline_ok = n0 + line0 < p.Ncols;
-    const uint16_t *bsrc = wsrc + (size_t)(bline_ok ? n0 + line0 : 0) * RS * Cred + oct * 8;
-    auto load_b = [&](int ch, int tap) {
-        uint4 v = zero4;
-        if (bline_ok && ch * BK + oct * 8 < Cred) v = *(const uint4 *)(bsrc + tap * Cred + ch * BK);
-        breg = v;
+    // Filter slice: line = output column (a filter in forward, an input channel in backward-data).  This
+    // lane's piece lands at line0, position oct, so it fetches piece oct ^ ((line0 >> 2) & 3) of that line;
+    // columns past the end re-read the last line (those output columns are never stored).
+    const uint16_t *bsrc = wsrc + (size_t)min(n0 + line0, p.Ncols - 1) * RS * Cred + ((oct ^ ((line0 >> 2) & 3)) * 8);
+    auto fetch_slice = [&](int ch, int tap, uint16_t *buf) __attribute__((always_inline)) {
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(bsrc + tap * Cred + ch * BK),
+                                         (__attribute__((address_space(3))) void *)(buf + wave * 512), 16, 0, 0);
     };
-    const int bst = line0 * PITCH + oct * 8;
     auto frag = [&](const uint16_t *q) { return __builtin_bit_cast(bf16x8, *(const uint4 *)q); };
-    auto tap_offsets = [&](int r, int s, int (&aoff)[MB]) {
+    // element offsets of this lane's filter fragments: [32-filter block][16-channel phase]
+    int boff[2][2];
 #pragma unroll
-        for (int bm = 0; bm < MB; bm++) {
-            const bool ok = (unsigned)(hh[bm] + r) < (unsigned)Hi && (unsigned)(ww[bm] + s) < (unsigned)Wi;
-            aoff[bm] = (ok ? prow[bm] + r * Wi + s : PR) * PITCH + lh * 8;
+    for (int bn = 0; bn < 2; bn++)
+#pragma unroll
+        for (int kc = 0; kc < 2; kc++) {
+            const int row = bn * 32 + li;
+            boff[bn][kc] = row * BK + (((kc * 2 + lh) ^ ((row >> 2) & 3)) * 8);
         }
+    auto tap_offsets = [&](int tap, int r, int s, int (&aoff)[MB]) __attribute__((always_inline)) {
+        const int shift = (r * Wi + s) * PITCH;
+#pragma unroll
+        for (int bm = 0; bm < MB; bm++) aoff[bm] = ((inside[bm] >> tap) & 1u) ? poff[bm] + shift : ZOFF + lh * 8;
     };
 
-    // order of a phase as the hardware should see it: the two filter-fragment reads, then four times
-    // (two MFMAs, one pixel-fragment read); the compiler's own order bunches the reads behind the MFMAs
-    auto pin_schedule = [&]() {
-        __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-        for (int bm = 0; bm < MB; bm++) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        }
-    };
+    // order of a phase as the hardware should see it: `lead` fragment reads, then four times (two MFMAs,
+    // one fragment read; `first` reads after the first pair); the compiler's own order bunches the reads
+    // behind the MFMAs
+#define OWT_PIN_PHASE(LEAD, FIRST)                                       \
+    do {                                                                \
+        if (LEAD) __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0); \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);          \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
+    } while (0)
 
     float16v acc[MB][2];
 #pragma unroll
@@ -131,49 +162,49 @@ __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
             for (int r = 0; r < 16; r++) acc[i][j][r] = 0.f;
 
     const int nsteps = (ch_end - ch_beg) * RS;                  // one step per (chunk, tap)
-    if (tid < PITCH) panel[PR * PITCH + tid] = 0;               // the row of zeros
+    if (tid < PITCH) panel[ZOFF + tid] = 0;                     // the row of zeros
     if (nsteps > 0) {
         load_panel(ch_beg);
-        load_b(ch_beg, 0);
+        fetch_slice(ch_beg, 0, slice0);
+        fetch_slice(ch_beg, 1, slice1);                         // at least two taps (host-checked)
         store_panel();
-        *(uint4 *)(lds + bst) = breg;
+        __builtin_amdgcn_s_waitcnt(0x0F70);                     // vmcnt(0): both slices have landed
     }
     __syncthreads();
 
     if (nsteps > 0) {
-        const int boff0 = li * PITCH + lh * 8, boff1 = boff0 + 32 * PITCH;
         bf16x8 af[MB], bf[2][2];
         int aoff[MB];
-        tap_offsets(0, 0, aoff);
+        tap_offsets(0, 0, 0, aoff);
 #pragma unroll
         for (int bm = 0; bm < MB; bm++) af[bm] = frag(panel + aoff[bm]);
-        bf[0][0] = frag(lds + boff0);
-        bf[0][1] = frag(lds + boff1);
-        // the slice of step 1 (guards inside load_b keep a step past the end harmless)
+        bf[0][0] = frag(slice0 + boff[0][0]);
+        bf[0][1] = frag(slice0 + boff[1][0]);
         int ch = ch_beg, tap = 0, r = 0, s = 0;
-        load_b(RS > 1 ? ch : ch + 1, RS > 1 ? 1 : 0);
 
-        int cur = 0;
-        for (int t = 0; t < nsteps; t++) {
+        // one (chunk, tap) step on the slice in `cur`; `nxt` holds the slice of the following step.  Forced inline:
+        // called out of line, everything it captures would live in scratch memory.
+        auto step = [&](int t, uint16_t *cur, uint16_t *nxt) __attribute__((always_inline)) {
             const bool swap_panel = tap == RS - 1 && t + 1 < nsteps;    // the next step starts a new chunk
-            const uint16_t *Bs = lds + cur * BT;
-            uint16_t *Bn = lds + (cur ^ 1) * BT;
 
-            // phase 0: channels 0..15 of the chunk; fetch the fragments of channels 16..31
-            bf[1][0] = frag(Bs + boff0 + 16);
-            bf[1][1] = frag(Bs + boff1 + 16);
+            // phase 0: channels 0..15 of the chunk; fetch the fragments of channels 16..31.  The first MFMAs
+            // wait for the fragments requested a phase ago only: this phase's reads are issued behind them.
 #pragma unroll
             for (int bm = 0; bm < MB; bm++) {
                 acc[bm][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[0][0], af[bm], acc[bm][0], 0, 0, 0);
                 acc[bm][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[0][1], af[bm], acc[bm][1], 0, 0, 0);
                 af[bm] = frag(panel + aoff[bm] + 16);
+                if (bm == 0) {
+                    bf[1][0] = frag(cur + boff[0][1]);
+                    bf[1][1] = frag(cur + boff[1][1]);
+                }
             }
-            pin_schedule();
+            OWT_PIN_PHASE(0, 3);
             if (swap_panel) {
                 __syncthreads();                                 // every wave has its last fragments of the old panel
                 store_panel();
             }
-            *(uint4 *)(Bn + bst) = breg;                         // slice of step t+1
+            __builtin_amdgcn_s_waitcnt(0x0F70);                  // vmcnt(0): this wave's pieces of `nxt` have landed
             __syncthreads();
 
             // coordinates of steps t+1 and t+2
@@ -183,20 +214,25 @@ __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
             int tap2 = tap1 + 1, ch2 = ch1;
             if (tap2 == RS) { tap2 = 0; ch2++; }
 
-            // phase 1: channels 16..31; fetch the first fragments of step t+1
-            load_b(ch2, tap2);
+            // phase 1: channels 16..31; fetch the first fragments of step t+1; the slice of step t+2
+            // goes into `cur`, whose last reads ended before the barrier
+            if (t + 2 < nsteps) fetch_slice(ch2, tap2, cur);
             if (tap == 0 && ch + 1 < ch_end) load_panel(ch + 1);  // held in registers until the last tap
-            tap_offsets(r1, s1, aoff);
-            bf[0][0] = frag(Bn + boff0);
-            bf[0][1] = frag(Bn + boff1);
+            tap_offsets(tap1, r1, s1, aoff);
+            bf[0][0] = frag(nxt + boff[0][0]);
+            bf[0][1] = frag(nxt + boff[1][0]);
 #pragma unroll
             for (int bm = 0; bm < MB; bm++) {
                 acc[bm][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[1][0], af[bm], acc[bm][0], 0, 0, 0);
                 acc[bm][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bf[1][1], af[bm], acc[bm][1], 0, 0, 0);
                 af[bm] = frag(panel + aoff[bm]);
             }
-            pin_schedule();
-            cur ^= 1; tap = tap1; ch = ch1; r = r1; s = s1;
+            OWT_PIN_PHASE(2, 1);
+            tap = tap1; ch = ch1; r = r1; s = s1;
+        };
+        for (int t = 0; t < nsteps; t += 2) {
+            step(t, slice0, slice1);
+            if (t + 1 < nsteps) step(t + 1, slice1, slice0);
         }
     }
 
@@ -240,5 +276,7 @@ __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
         }
     }
 }
+
+#undef OWT_PIN_PHASE
 
 }  // namespace owt

@@ -314,7 +314,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
             const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
             int pr;
-            if (t == TILE_512x64) { if (rows < 0 || rows > 624 || dm.Ncols % 4) continue; pr = rows <= 544 ? 544 : 624; }
+            if (t == TILE_512x64) { if (rows < 0 || rows > 624 || dm.Ncols % 4 || cred % 32 || g.R * g.S > 32) continue; pr = rows <= 544 ? 544 : 624; }
             else if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
             else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : 256; }
             const long bk = t == TILE_512x64 ? 32 : 64, chunks = cdiv(cred, bk);

@@ -156,11 +156,16 @@ def test_bf16_mfma_direct_kernel(tile, split):
     m = owt()
     os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(tile), str(split)
     try:
-        for (N, C, H, W, K, R, S, pad), kw in [
-                ((4, 72, 13, 13, 136, 3, 3, 1), {}),                         # ragged last chunk in both passes
-                ((3, 64, 27, 27, 72, 5, 5, 2), {}),                          # 240-row panel
-                ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False)),         # one short chunk, R != S
-                ((2, 192, 13, 13, 200, 3, 3, 1), dict(bias=False))]:         # three / four chunks
+        shapes = [((4, 72, 13, 13, 136, 3, 3, 1), {}),                       # ragged last chunk in both passes
+                  ((3, 64, 27, 27, 72, 5, 5, 2), {}),                        # 240-row panel
+                  ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False)),       # one short chunk, R != S
+                  ((2, 192, 13, 13, 200, 3, 3, 1), dict(bias=False))]        # three / four chunks
+        if tile == 7:   # the pipelined 512x64 tile: channels and filters in whole 32-channel chunks
+            shapes = [((4, 64, 13, 13, 160, 3, 3, 1), {}),                   # two M tiles, ragged N tile, 2 / 5 chunks
+                      ((3, 64, 27, 27, 96, 5, 5, 2), {}),                    # 624-row panel, 25 taps
+                      ((2, 32, 9, 14, 32, 3, 5, (1, 2)), dict(relu=False)),  # one chunk, R != S, half-empty tile
+                      ((5, 192, 13, 13, 224, 3, 3, 1), dict(bias=False))]    # six / seven chunks, odd step counts
+        for (N, C, H, W, K, R, S, pad), kw in shapes:
             d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_BF16, m.OWT_BIAS | m.OWT_RELU)
             for ps in (m.OWT_PASS_FWD, m.OWT_PASS_BWD_DATA):
                 assert m.owt_conv_plan_describe(d, ps).startswith("dconv16"), m.owt_conv_plan_describe(d, ps)
