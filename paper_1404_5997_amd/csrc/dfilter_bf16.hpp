@@ -42,8 +42,8 @@ __device__ __forceinline__ short4_t lds_read_tr16(const uint16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t *)p);
 }
 
-template <int WK, int WC, int KB, int TAPS, int PRF>
-__global__ void __launch_bounds__(64 * WK * WC, 1) dfilter16_kernel(const GemmParams p)
+template <int WK, int WC, int KB, int TAPS, int PRF, int OCC>
+__global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WK * WC, KT = 32 * KB * WK, CT = 32 * WC, BP = 64;
     constexpr int PA = KT + 16, PB = CT + 16;                    // row pitches in elements: data + 32 bytes

@@ -4,11 +4,12 @@
 
 namespace owt {
 
-template <int WK, int WC, int KB, int TMAX, int PRF>
+template <int V>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
+    constexpr DFilter16Variant v = kDFilter16Variants[V];
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    hipLaunchKernelGGL((dfilter16_kernel<WK, WC, KB, TMAX, PRF>), grid, dim3(64 * WK * WC), 0, s, p);
+    hipLaunchKernelGGL((dfilter16_kernel<v.WK, v.WC, v.KB, v.tmax, v.prf, v.occ>), grid, dim3(64 * v.WK * v.WC), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
     return e;
@@ -17,14 +18,13 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &p, hipStream_t s)
 {
     switch (variant) {
-    case 0: return go<kDFilter16Variants[0].WK, kDFilter16Variants[0].WC, kDFilter16Variants[0].KB, kDFilter16Variants[0].tmax,
-                      kDFilter16Variants[0].prf>(p, s);
-    case 1: return go<kDFilter16Variants[1].WK, kDFilter16Variants[1].WC, kDFilter16Variants[1].KB, kDFilter16Variants[1].tmax,
-                      kDFilter16Variants[1].prf>(p, s);
-    case 2: return go<kDFilter16Variants[2].WK, kDFilter16Variants[2].WC, kDFilter16Variants[2].KB, kDFilter16Variants[2].tmax,
-                      kDFilter16Variants[2].prf>(p, s);
-    case 3: return go<kDFilter16Variants[3].WK, kDFilter16Variants[3].WC, kDFilter16Variants[3].KB, kDFilter16Variants[3].tmax,
-                      kDFilter16Variants[3].prf>(p, s);
+    case 0: return go<0>(p, s);
+    case 1: return go<1>(p, s);
+    case 2: return go<2>(p, s);
+    case 3: return go<3>(p, s);
+    case 4: return go<4>(p, s);
+    case 5: return go<5>(p, s);
+    case 6: return go<6>(p, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -446,7 +446,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     if (pass == OWT_PASS_BWD_FILTER && !no_direct && !getenv("OWT_NO_BF16_MFMA")) {
-        for (int v = 0; v < 4; v++) {
+        for (int v = 0; v < kNumDFilter16Variants; v++) {
             int taps, groups;
             if (force_tile >= 0 && force_tile != v) continue;
             if (!dfilter16_fits(g, v, taps, groups)) continue;
@@ -466,7 +466,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
                     l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                     l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
                 }
-                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, dv.WK * dv.WC <= 2 ? 2 : 1,
+                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, dv.occ,
                                     (double)KT * CT * kDFilter16BP * taps * per / 5.0, 1.2,
                                     splits, dm.M, dm.Ncols);
                 bool dup = false;

@@ -53,9 +53,16 @@ hipError_t owt_launch_dfilter_f32(int variant, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dfilter_bf16(int variant, const GemmParams &, hipStream_t);
 
 // bf16-MFMA direct filter-gradient kernel (dfilter_bf16_inst.hip): work-group tile 32*KB*WK filters x
-// 32*WC channels, 64-pixel chunks, tmax taps per work-group, prf panel rows.
-struct DFilter16Variant { int WK, WC, KB, tmax, prf; };
-constexpr DFilter16Variant kDFilter16Variants[4] = {{1, 4, 4, 3, 128}, {2, 2, 2, 5, 224}, {1, 2, 4, 3, 128}, {3, 2, 2, 5, 224}};
+// 32*WC channels, 64-pixel chunks, tmax taps per work-group, prf panel rows, occ work-groups per CU.
+// Variants 4 and 5 cover the tiles of 0 and 2 with twice the wavefronts of half the filter block each
+// (two wavefronts per SIMD instead of one: more LDS reads per MFMA, but one wavefront's waits are
+// filled by the other), variant 6 the tile of 3 with twelve wavefronts of one filter block.  Sixteen
+// wavefronts of one block on the 128 x 128 tile were slower again: the LDS reads then bound the kernel.
+struct DFilter16Variant { int WK, WC, KB, tmax, prf, occ; };
+constexpr int kNumDFilter16Variants = 7;
+constexpr DFilter16Variant kDFilter16Variants[kNumDFilter16Variants] = {
+    {1, 4, 4, 3, 128, 1}, {2, 2, 2, 5, 224, 1}, {1, 2, 4, 3, 128, 2}, {3, 2, 2, 5, 224, 1}, {2, 4, 2, 3, 128, 1}, {2, 2, 2, 3, 128, 2},
+    {6, 2, 1, 5, 224, 1}};
 constexpr int kDFilter16BP = 64;
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 

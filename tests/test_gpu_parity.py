@@ -175,15 +175,15 @@ def test_bf16_mfma_direct_kernel(tile, split):
             os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (0, 3), (1, 4), (2, 7), (3, 5)])
+@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (6, 1), (0, 3), (1, 4), (2, 7), (3, 5), (4, 2), (5, 6), (6, 3)])
 def test_bf16_mfma_filter_gradient_kernel(variant, split):
     # bf16 storage, stride 1, "same" padding, channels and filters multiples of 8: the filter gradient runs on
-    # the bf16 MFMA, one filter row per work-group (3-tap variants 0 and 2, 5-tap variant 1)
+    # the bf16 MFMA, one filter row per work-group (3-tap variants 0, 2, 4, 5; 5-tap variants 1, 3, 6)
     m = owt()
     os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(variant), str(split)
     try:
         shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25))] \
-            if variant in (1, 3) else \
+            if variant in (1, 3, 6) else \
             [((4, 72, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
              ((3, 8, 6, 11, 8, 3, 3, 1), dict(relu=False, alpha=1.0 / 3, beta=1.0))]
         for (N, C, H, W, K, R, S, pad), kw in shapes:
