@@ -27,11 +27,11 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
     return e;
 }
 
-template <int PR>
+template <int PR, int MB, int OCC>
 static hipError_t go_pipelined(const GemmParams &p, hipStream_t s)
 {
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    hipLaunchKernelGGL((dconv16p_kernel<OE, kBwd, PR>), grid, dim3(256), 0, s, p);
+    hipLaunchKernelGGL((dconv16p_kernel<OE, kBwd, PR, MB, OCC>), grid, dim3(256), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<OE>(p, s);
     return e;
@@ -48,9 +48,15 @@ static hipError_t dispatch(int tile, int pr, const GemmParams &p, hipStream_t s)
     } else if (tile == TILE_256x64) {
         if (pr <= 288) return go<4, 1, 288>(p, s);
         if (pr <= 384) return go<4, 1, 384>(p, s);
-    } else if (tile == TILE_512x64 && p.Ncols % 4 == 0 && p.Cred % 32 == 0 && p.g.R * p.g.S >= 2 && p.g.R * p.g.S <= 32) {
-        if (pr <= 544) return go_pipelined<544>(p, s);
-        if (pr <= 624) return go_pipelined<624>(p, s);
+    } else if ((tile == TILE_512x64 || tile == TILE_256x64P) && p.Ncols % 4 == 0 && p.Cred % 32 == 0 &&
+               p.g.R * p.g.S >= 2 && p.g.R * p.g.S <= 32) {
+        if (tile == TILE_512x64) {
+            if (pr <= 544) return go_pipelined<544, 4, 2>(p, s);
+            if (pr <= 624) return go_pipelined<624, 4, 2>(p, s);
+        } else {
+            if (pr <= 288) return go_pipelined<288, 2, 3>(p, s);
+            if (pr <= 384) return go_pipelined<384, 2, 3>(p, s);
+        }
     }
     return hipErrorInvalidValue;
 }

@@ -27,13 +27,16 @@
 
 namespace owt {
 
-template <class Epi, bool BWD, int PR>
-__global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
+// MB = 32-pixel blocks per wavefront (4: the 512 x 64 tile, two work-groups per CU; 2: 256 x 64, fewer
+// registers, three work-groups per CU), OCC = work-groups per CU the register budget is cut for.
+template <class Epi, bool BWD, int PR, int MB, int OCC>
+__global__ void __launch_bounds__(256, OCC) dconv16p_kernel(const GemmParams p)
 {
-    constexpr int BK = 32, NT = 256, MB = 4, BM = 512, BN = 64, PITCH = BK + 8;   // panel rows: 80 bytes
+    constexpr int BK = 32, NT = 256, BM = 128 * MB, BN = 64, PITCH = BK + 8;      // panel rows: 80 bytes
     constexpr int OCTS = BK / 8, RPP = NT / OCTS, PNP = (PR + RPP - 1) / RPP;
     constexpr int BT = BN * BK;                                  // bf16 elements per filter-slice buffer
     static_assert(BN * OCTS == NT, "one 16-byte piece of the filter slice per thread");
+    static_assert(MB == 2 || MB == 4, "two or four 32-pixel blocks per wavefront");
 
     __shared__ __attribute__((aligned(16))) uint16_t slice0[BT];
     __shared__ __attribute__((aligned(16))) uint16_t slice1[BT];
@@ -140,17 +143,19 @@ __global__ void __launch_bounds__(256, 2) dconv16p_kernel(const GemmParams p)
     // order of a phase as the hardware should see it: `lead` fragment reads, then four times (two MFMAs,
     // one fragment read; `first` reads after the first pair); the compiler's own order bunches the reads
     // behind the MFMAs
-#define OWT_PIN_PHASE(LEAD, FIRST)                                       \
-    do {                                                                \
-        if (LEAD) __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0); \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
-        __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);          \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
+#define OWT_PIN_PHASE(LEAD, FIRST)                                           \
+    do {                                                                    \
+        if (LEAD) __builtin_amdgcn_sched_group_barrier(0x100, LEAD, 0);     \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                  \
+        __builtin_amdgcn_sched_group_barrier(0x100, FIRST, 0);              \
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);                  \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                  \
+        if (MB > 2) {                                                       \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);              \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);              \
+        }                                                                   \
     } while (0)
 
     float16v acc[MB][2];

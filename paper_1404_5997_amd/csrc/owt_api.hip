@@ -25,7 +25,7 @@ owt_status fail(owt_status st, const char *fmt, ...)
 }
 void clear_error() { g_err[0] = 0; }
 
-const TileInfo kTiles[NUM_TILES + 4] = {
+const TileInfo kTiles[NUM_TILES + 5] = {
     {TILE_128x128, 2, 2, 32, 1.00f, 128},
     {TILE_128x64, 2, 1, 16, 0.90f, 128},
     {TILE_64x128, 1, 2, 16, 0.90f, 64},
@@ -34,6 +34,7 @@ const TileInfo kTiles[NUM_TILES + 4] = {
     {TILE_128x64H, 4, 1, 32, 1.00f, 128},
     {TILE_128x128H, 4, 2, 32, 1.00f, 128},
     {TILE_512x64, 4, 1, 32, 1.00f, 512},
+    {TILE_256x64P, 4, 1, 32, 1.00f, 256},
 };
 
 static inline long cdiv(long a, long b) { return (a + b - 1) / b; }
@@ -310,20 +311,22 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     if (g.bf16 && cred % 8 == 0 && !getenv("OWT_NO_BF16_MFMA")) {      // the bf16 MFMA: 64-channel chunks, or 32 in the 512x64 tile
-        for (int t : {TILE_128x128, TILE_128x64, TILE_256x64, TILE_512x64}) {
+        for (int t : {TILE_128x128, TILE_128x64, TILE_256x64, TILE_512x64, TILE_256x64P}) {
             if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
             const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
             int pr;
-            if (t == TILE_512x64) { if (rows < 0 || rows > 624 || dm.Ncols % 4 || cred % 32 || g.R * g.S > 32) continue; pr = rows <= 544 ? 544 : 624; }
-            else if (t == TILE_256x64) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
+            const bool pipelined = t == TILE_512x64 || t == TILE_256x64P;
+            if (pipelined && (dm.Ncols % 4 || cred % 32 || g.R * g.S > 32)) continue;
+            if (t == TILE_512x64) { if (rows < 0 || rows > 624) continue; pr = rows <= 544 ? 544 : 624; }
+            else if (t == TILE_256x64 || t == TILE_256x64P) { if (rows < 0 || rows > 384) continue; pr = rows <= 288 ? 288 : 384; }
             else { if (rows < 0 || rows > 256) continue; pr = rows <= 160 ? 160 : 256; }
-            const long bk = t == TILE_512x64 ? 32 : 64, chunks = cdiv(cred, bk);
+            const long bk = pipelined ? 32 : 64, chunks = cdiv(cred, bk);
             // ~6x the fp32 MFMA rate; the pipelined tile keeps the matrix unit about 1.5x busier
-            const double macs = (double)BM * 64 * kTiles[t].WN * bk * g.R * g.S / (t == TILE_512x64 ? 9.0 : 6.0);
+            const double macs = (double)BM * 64 * kTiles[t].WN * bk * g.R * g.S / (pipelined ? 9.0 : 6.0);
             const size_t n0 = out.size();
             for (long s : kSplits) {
                 if (s > 1 && (chunks / s < 1 || s > 8 || s > chunks)) break;
-                add(KIND_DIRECT16, t, pr, chunks, s, macs, 2, 1.25);
+                add(KIND_DIRECT16, t, pr, chunks, s, macs, t == TILE_256x64P ? 3 : 2, 1.25);
                 if (force_split > 0) break;
             }
             if (pass == OWT_PASS_BWD_DATA)
@@ -633,7 +636,7 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     const long threads = (long)l.tiles_m * l.tiles_n * l.splits * 64 * ti.WM * ti.WN;
     if (l.kind == KIND_DIRECT16)
         return snprintf(buf, n, "dconv16 %s %s tile%dx%dx%d waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
-                        ti.BM, 64 * ti.WN, l.tile == TILE_512x64 ? 32 : 64, ti.WM, ti.WN, l.pr, l.splits,
+                        ti.BM, 64 * ti.WN, (l.tile == TILE_512x64 || l.tile == TILE_256x64P) ? 32 : 64, ti.WM, ti.WN, l.pr, l.splits,
                         l.tiles_m * l.tiles_n, l.splits, threads);
     if (l.kind == KIND_DIRECT)
         return snprintf(buf, n, "dconv %s %s tile%dx%dx%d waves%dx%d panel%d splitk%d grid%dx%d threads%ld", pn[pass], ds,

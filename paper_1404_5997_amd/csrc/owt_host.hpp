@@ -19,9 +19,9 @@ inline bool aligned16(const void *p) { return (((uintptr_t)p) & 15u) == 0; }
 struct TileInfo { int id, WM, WN, BK; float eff; int BM; };
 // ids 0..3 exist for the gather kernel; the stride-1 direct kernel has 128x128, 128x64, 256x64 and
 // 128x64H (four wavefronts of 32x64 instead of two of 64x64: twice the wavefronts for small layers);
-// 512x64 (four wavefronts of 128x64, 32-channel chunks) is the pipelined bf16-MFMA kernel only
-enum { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x128 = 2, TILE_64x64 = 3, NUM_TILES = 4, TILE_256x64 = 4, TILE_128x64H = 5, TILE_128x128H = 6, TILE_512x64 = 7 };
-extern const TileInfo kTiles[NUM_TILES + 4];
+// 512x64 and 256x64P (four wavefronts of 128x64 / 64x64, 32-channel chunks) are the pipelined bf16-MFMA kernel only
+enum { TILE_128x128 = 0, TILE_128x64 = 1, TILE_64x128 = 2, TILE_64x64 = 3, NUM_TILES = 4, TILE_256x64 = 4, TILE_128x64H = 5, TILE_128x128H = 6, TILE_512x64 = 7, TILE_256x64P = 8 };
+extern const TileInfo kTiles[NUM_TILES + 5];
 
 bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw);
 

@@ -149,7 +149,7 @@ def test_every_tile_shape_and_split_k(tile, split, direct):
             os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2), (7, 1), (7, 2), (7, 3)])
+@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2), (7, 1), (7, 2), (7, 3), (8, 1), (8, 2)])
 def test_bf16_mfma_direct_kernel(tile, split):
     # bf16 storage, stride 1, reduction channels a multiple of 8: forward and backward-data run on the
     # bf16 MFMA kernel (64-channel chunks; backward-data reads re-laid-out filters from the workspace)
@@ -160,7 +160,7 @@ def test_bf16_mfma_direct_kernel(tile, split):
                   ((3, 64, 27, 27, 72, 5, 5, 2), {}),                        # 240-row panel
                   ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False)),       # one short chunk, R != S
                   ((2, 192, 13, 13, 200, 3, 3, 1), dict(bias=False))]        # three / four chunks
-        if tile == 7:   # the pipelined 512x64 tile: channels and filters in whole 32-channel chunks
+        if tile in (7, 8):   # the pipelined 512x64 / 256x64 tiles: channels and filters in whole 32-channel chunks
             shapes = [((4, 64, 13, 13, 160, 3, 3, 1), {}),                   # two M tiles, ragged N tile, 2 / 5 chunks
                       ((3, 64, 27, 27, 96, 5, 5, 2), {}),                    # 624-row panel, 25 taps
                       ((2, 32, 9, 14, 32, 3, 5, (1, 2)), dict(relu=False)),  # one chunk, R != S, half-empty tile
