@@ -26,7 +26,7 @@ def short(name):
 
 def family(name):
     n = short(name)
-    if n.startswith("dconv_bf16_kernel"):
+    if n.startswith("dconv_bf16_kernel") or n.startswith("dconv16p_kernel"):
         return "dconv16 " + ("fwd" if "EpiFwd" in n else "bwd_data")
     if n.startswith("dconv_kernel"):
         return "dconv " + ("fwd" if "EpiFwd" in n else "bwd_data")
