@@ -1,10 +1,10 @@
 """Turns rocprofv3 CSV output of a bench.py run into the short summaries kept under profiles/.
 
     python -m paper_1404_5997_amd.prof_summary --workload conv_stack \\
-        --trace gpurun_out/prof_kt/kt_kernel_trace.csv \\
-        --fetch gpurun_out/pmc_fetch/fetch_counter_collection.csv \\
-        --write gpurun_out/pmc_write/write_counter_collection.csv \\
-        [--sq gpurun_out/pmc_sq/sq_counter_collection.csv] --out profiles
+        --trace out/prof_kt/kt_kernel_trace.csv \\
+        --fetch out/pmc_fetch/fetch_counter_collection.csv \\
+        --write out/pmc_write/write_counter_collection.csv \\
+        [--sq out/pmc_sq/sq_counter_collection.csv] --out profiles
 
 Only the dispatches of the last steps of the run are used (the steps after the
 library's tuning runs); bench.py --copy-calibration ends with three plain
