@@ -245,6 +245,53 @@ __global__ void __launch_bounds__(256, OCC) dconv16p_kernel(const GemmParams p)
     const bool part = p.splits > 1;
     float *pout = part ? p.partial + (size_t)split * p.M * p.Ncols : nullptr;
     uint16_t *out = (uint16_t *)p.out;
+    if (!part && (p.Ncols & 7) == 0) {
+        // Results leave through LDS, 32 pixels x 64 filters per wavefront and pass: a lane writes its 8-byte
+        // pieces (bias and ReLU applied), then the wavefront reads the block back row-wise and stores 16 bytes
+        // per lane, eight lanes to a 128-byte line (stored straight from the accumulators a store instruction
+        // would touch 32 lines with 16 bytes each).  The panel is free: after the last barrier of the loop no
+        // wavefront reads anything from it that it still uses; each wavefront stages in its own part, so
+        // program order is all the synchronisation this needs.  The ReLU' mask of backward-data is applied
+        // on the way out, with the same 16-byte accesses.
+        constexpr int EP = 64 + 4;                               // 136-byte rows: conflict-free 8-byte writes
+        static_assert(4 * 32 * EP <= (PR + 1) * PITCH, "the staging blocks must fit the panel");
+        uint16_t *stage = panel + wave * 32 * EP;
+        const uint16_t *xm = BWD ? (const uint16_t *)p.xmask : nullptr;
+#pragma unroll
+        for (int bm = 0; bm < MB; bm++) {
+#pragma unroll
+            for (int bn = 0; bn < 2; bn++)
+#pragma unroll
+                for (int j = 0; j < 4; j++) {
+                    const int nl = bn * 32 + 8 * j + 4 * lh, n = n0 + nl;
+                    float v0 = acc[bm][bn][4 * j], v1 = acc[bm][bn][4 * j + 1], v2 = acc[bm][bn][4 * j + 2], v3 = acc[bm][bn][4 * j + 3];
+                    if (!BWD) {
+                        if ((p.flags & 1u) && n < p.Ncols) { v0 += p.bias[n]; v1 += p.bias[n + 1]; v2 += p.bias[n + 2]; v3 += p.bias[n + 3]; }
+                        if (p.flags & 2u) {
+                            v0 = v0 > 0.f ? v0 : 0.f; v1 = v1 > 0.f ? v1 : 0.f;
+                            v2 = v2 > 0.f ? v2 : 0.f; v3 = v3 > 0.f ? v3 : 0.f;
+                        }
+                    }
+                    *(uint2 *)(stage + li * EP + nl) = make_uint2(f32x2_to_bf16x2(v0, v1), f32x2_to_bf16x2(v2, v3));
+                }
+#pragma unroll
+            for (int q = 0; q < 4; q++) {
+                const int row = q * 8 + (lane >> 3), nl = (lane & 7) * 8;
+                const int m = m0 + wm0 + bm * 32 + row, n = n0 + nl;
+                uint4 v = *(const uint4 *)(stage + row * EP + nl);
+                if (m < p.M && n < p.Ncols) {
+                    const size_t o = (size_t)m * p.Ncols + n;
+                    if (BWD && xm) {
+                        const uint4 x = *(const uint4 *)(xm + o);
+                        v.x = mask_pair(v.x, x.x); v.y = mask_pair(v.y, x.y);
+                        v.z = mask_pair(v.z, x.z); v.w = mask_pair(v.w, x.w);
+                    }
+                    *(uint4 *)(out + o) = v;
+                }
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int bn = 0; bn < 2; bn++) {
 #pragma unroll
