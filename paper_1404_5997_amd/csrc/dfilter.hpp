@@ -22,8 +22,9 @@
 
 namespace owt {
 
-template <class T, int WK, int WC, int TAPS, int PRF>
-__global__ void __launch_bounds__(64 * WK * WC, 2) dfilter_kernel(const GemmParams p)
+// OCC = work-groups per CU the register budget is cut for.
+template <class T, int WK, int WC, int TAPS, int PRF, int OCC>
+__global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WK * WC, KT = 32 * WK, CT = 32 * WC, BP = 32;
     constexpr int PA = KT + 4, PB = CT + 4;
@@ -67,15 +68,28 @@ __global__ void __launch_bounds__(64 * WK * WC, 2) dfilter_kernel(const GemmPara
     int tab_next = 0;
     const int pad_pix_total = g.N * p.Hp * Wp;
 
+    // Pixels [pix0, lim) of chunk ch.  With p.cpi the chunks are cut per image (the last chunk of an image is
+    // short), so a chunk never spans the padding rows between two images and its panel stays small.
+    auto chunk_range = [&](int ch, int &pix0, int &lim) {
+        if (p.cpi) {
+            const int n = p.dCpi.div(ch), cw = ch - n * p.cpi;
+            pix0 = n * g.P * g.Q + cw * BP;
+            lim = min(pix0 + BP, (n + 1) * g.P * g.Q);
+        } else {
+            pix0 = ch * BP;
+            lim = min(pix0 + BP, npix);
+        }
+    };
     auto load_chunk = [&](int ch) {
-        const int pix0 = ch * BP;
+        int pix0, lim;
+        chunk_range(ch, pix0, lim);
         const int ps = ppad(pix0) + r0 * Wp;
-        const int nrows = ppad(min(pix0 + BP, npix) - 1) + (r0 + rows_g - 1) * Wp + g.S - ps;   // <= PRF (host-checked)
+        const int nrows = ppad(lim - 1) + (r0 + rows_g - 1) * Wp + g.S - ps;   // <= PRF (host-checked)
 #pragma unroll
         for (int i = 0; i < ANP; i++) {
             const int pix = pix0 + arow0 + i * ARPP, k = k0 + akq * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (pix < npix && k < g.K) {
+            if (pix < lim && k < g.K) {
                 const int off = pix * g.K + k;
                 v = load4(dzsrc, off);
                 if (mask) {
@@ -101,7 +115,7 @@ __global__ void __launch_bounds__(64 * WK * WC, 2) dfilter_kernel(const GemmPara
         }
         if (tid < BP) {
             const int pix = pix0 + tid;
-            tab_next = pix < npix ? ppad(pix) + r0 * Wp - ps : 0;
+            tab_next = pix < lim ? ppad(pix) + r0 * Wp - ps : 0;
         }
     };
     auto store_chunk = [&]() {

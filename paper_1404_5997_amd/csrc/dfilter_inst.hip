@@ -17,11 +17,12 @@ typedef float TT;
 #define OWT_FN owt_launch_dfilter_f32
 #endif
 
-template <int WK, int WC, int TMAX, int PRF>
+template <int V>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
+    constexpr DFilterVariant v = kDFilterVariants[V];
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    hipLaunchKernelGGL((dfilter_kernel<TT, WK, WC, TMAX, PRF>), grid, dim3(64 * WK * WC), 0, s, p);
+    hipLaunchKernelGGL((dfilter_kernel<TT, v.WK, v.WC, v.tmax, v.prf, v.occ>), grid, dim3(64 * v.WK * v.WC), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
     return e;
@@ -30,9 +31,10 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
 hipError_t OWT_FN(int variant, const GemmParams &p, hipStream_t s)
 {
     switch (variant) {
-    case 0: return go<4, 1, kDFilterVariants[0].tmax, kDFilterVariants[0].prf>(p, s);
-    case 1: return go<2, 2, kDFilterVariants[1].tmax, kDFilterVariants[1].prf>(p, s);
-    case 2: return go<2, 2, kDFilterVariants[2].tmax, kDFilterVariants[2].prf>(p, s);
+    case 0: return go<0>(p, s);
+    case 1: return go<1>(p, s);
+    case 2: return go<2>(p, s);
+    case 3: return go<3>(p, s);
     default: return hipErrorInvalidValue;
     }
 }

@@ -142,7 +142,12 @@ static bool dfilter_fits(const Geom &g, int variant, int &taps, int &groups)
     else if (g.S == v.tmax) { taps = g.S; groups = g.R; }
     else return false;
     const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q;
-    const long span = 31 + (31 / g.Q + 1) * (Wp - g.Q) + (31 / PQ + 1) * (Hp - g.P) * Wp;
+    long span = 31 + (31 / g.Q + 1) * (Wp - g.Q);
+    if (v.aligned) {        // chunks cut per image: worth it only when the short last chunk wastes little
+        if (((PQ + 31) / 32) * 32 * 100 > PQ * 104) return false;
+    } else {
+        span += (31 / PQ + 1) * (Hp - g.P) * Wp;
+    }
     const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
     return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
 }
@@ -417,15 +422,16 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     if (pass == OWT_PASS_BWD_FILTER && !no_direct) {
-        for (int v = 0; v < 3; v++) {
+        for (int v = 0; v < kNumDFilterVariants; v++) {
             int taps, groups;
             if (force_tile >= 0 && force_tile != v) continue;
             if (!dfilter_fits(g, v, taps, groups)) continue;
             if (v == 2 && g.K % 128 == 0) continue;                  // variant 0 covers it with the same accumulators
             const DFilterVariant &dv = kDFilterVariants[v];
             const long KT = 32 * dv.WK, CT = 32 * dv.WC;
-            const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, 32);
-            for (long s0 : split_ladder(tm * ctl * groups)) {
+            const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT);
+            const long steps = dv.aligned ? (long)g.N * cdiv((long)g.P * g.Q, 32) : cdiv(dm.Kd, 32);
+            for (long s0 : split_ladder(tm * ctl * groups, 256 * dv.occ)) {
                 long s = s0;
                 if (force_split > 0) s = force_split < steps ? force_split : steps;
                 else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 2560)) break;
@@ -438,7 +444,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
                     l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                     l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
                 }
-                l.cost = model_cost(tm * ctl * groups * splits, 4, 2, (double)KT * CT * 32 * taps * per, 1.2, splits,
+                l.cost = model_cost(tm * ctl * groups * splits, 4, dv.occ, (double)KT * CT * 32 * taps * per, 1.2, splits,
                                     dm.M, dm.Ncols);
                 bool dup = false;
                 for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
@@ -585,6 +591,7 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
     } else if (l.kind == KIND_DFILTER) {
         p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
         p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
+        if (kDFilterVariants[l.tile].aligned) { p.cpi = (int)cdiv((long)g.P * g.Q, 32); p.dCpi.set(p.cpi); }
         e = bf ? owt_launch_dfilter_bf16(l.tile, p, s) : owt_launch_dfilter_f32(l.tile, p, s);
     } else if (l.kind == KIND_DIRECT) {
         dconv_frame(g, pass, p);
@@ -628,8 +635,8 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     }
     if (l.kind == KIND_DFILTER) {
         const DFilterVariant &v = kDFilterVariants[l.tile];
-        return snprintf(buf, n, "dfilter %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds, 32 * v.WK,
-                        32 * v.WC, l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits,
+        return snprintf(buf, n, "dfilter %s %s tile%dx%d taps%dx%d%s splitk%d grid%dx%d threads%ld", pn[pass], ds, 32 * v.WK,
+                        32 * v.WC, l.taps, l.groups, v.aligned ? " chunks-per-image" : "", l.splits, l.tiles_m * l.tiles_n, l.splits,
                         (long)l.tiles_m * l.tiles_n * l.splits * 64 * v.WK * v.WC);
     }
     const TileInfo &ti = kTiles[l.tile];

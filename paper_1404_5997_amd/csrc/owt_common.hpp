@@ -57,6 +57,9 @@ struct GemmParams {
     // `taps` at a time, either all R*S at once (groups == 1) or one filter row per group.
     int Hp, Wp, taps, groups, ctiles;
     FastDiv dWp, dHpWp;
+    // cpi > 0: the pixel chunks never straddle two images (cpi chunks per image, the last one short)
+    int cpi;
+    FastDiv dCpi;
 };
 
 struct bf16_t { uint16_t bits; };

@@ -47,8 +47,13 @@ hipError_t owt_launch_dconv16_data(int tile, int pr, const GemmParams &, void *w
 
 // Direct filter-gradient kernel (dfilter_inst.hip): wavefront grid WK x WC (32 filters x 32
 // channels each), exactly tmax taps per work-group, LDS panel of prf padded-image pixels.
-struct DFilterVariant { int WK, WC, tmax, prf; };
-constexpr DFilterVariant kDFilterVariants[3] = {{4, 1, 9, 128}, {2, 2, 5, 192}, {2, 2, 9, 128}};
+// occ = work-groups per CU; aligned = the 32-pixel chunks are cut per image (taken only when the short
+// last chunk of an image wastes under 4 %): no chunk then spans the padding rows between two images, so
+// variant 3 gets by with a 64-row panel where variant 1 needs 192, and three work-groups fit a CU.
+struct DFilterVariant { int WK, WC, tmax, prf, occ, aligned; };
+constexpr int kNumDFilterVariants = 4;
+constexpr DFilterVariant kDFilterVariants[kNumDFilterVariants] = {
+    {4, 1, 9, 128, 2, 0}, {2, 2, 5, 192, 2, 0}, {2, 2, 9, 128, 2, 0}, {2, 2, 5, 64, 3, 1}};
 hipError_t owt_launch_dfilter_f32(int variant, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dfilter_bf16(int variant, const GemmParams &, hipStream_t);
 

@@ -149,6 +149,24 @@ def test_every_tile_shape_and_split_k(tile, split, direct):
             os.environ.pop(k, None)
 
 
+@pytest.mark.parametrize("split", [1, 7, 40])
+def test_filter_gradient_with_chunks_cut_per_image(split):
+    # 5x5 "same" layer on 27x27 images: 729 pixels = 22 chunks of 32 + one of 25 per image; the variant whose
+    # pixel chunks never straddle two images (small panel, three work-groups per CU), forced, fp32 and bf16 storage
+    m = owt()
+    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = "3", str(split)
+    try:
+        for (N, C, K), kw in [((3, 64, 72), {}), ((1, 8, 200), dict(relu=False, alpha=0.5, beta=-0.25)), ((5, 36, 64), dict(bias=False))]:
+            d = m.conv_desc(N, C, 27, 27, K, 5, 5, 1, 2, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
+            assert "chunks-per-image" in m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER), m.owt_conv_plan_describe(d, 2)
+            layer_parity(N, C, 27, 27, K, 5, 5, 1, 2, seed=800 + split, **kw)
+        os.environ["OWT_NO_BF16_MFMA"] = "1"
+        layer_parity(2, 64, 27, 27, 72, 5, 5, 1, 2, dt="bf16", seed=810 + split)
+    finally:
+        for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_BF16_MFMA"):
+            os.environ.pop(k, None)
+
+
 @pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2), (7, 1), (7, 2), (7, 3), (8, 1), (8, 2)])
 def test_bf16_mfma_direct_kernel(tile, split):
     # bf16 storage, stride 1, reduction channels a multiple of 8: forward and backward-data run on the
