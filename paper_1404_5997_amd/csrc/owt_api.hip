@@ -444,7 +444,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
                     l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                     l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
                 }
-                l.cost = model_cost(tm * ctl * groups * splits, 4, dv.occ, (double)KT * CT * 32 * taps * per, 1.2, splits,
+                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, dv.occ, (double)KT * CT * 32 * taps * per, 1.2, splits,
                                     dm.M, dm.Ncols);
                 bool dup = false;
                 for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
