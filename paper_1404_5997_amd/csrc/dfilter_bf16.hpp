@@ -48,9 +48,13 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const Gemm
     constexpr int NT = 64 * WK * WC, KT = 32 * KB * WK, CT = 32 * WC, BP = 64;
     constexpr int PA = KT + 16, PB = CT + 16;                    // row pitches in elements: data + 32 bytes
     constexpr int KO = KT / 8, ARPP = NT / KO, ANP = BP / ARPP;                  // dz loader (16-byte pieces)
-    constexpr int CO = CT / 8, BRPP = NT / CO, BNP = (PRF + BRPP - 1) / BRPP;    // x panel loader
+    // x panel loader: a thread fetches LPT 16-byte pieces of one panel row (pieces bq, bq + TPR, ...), so the
+    // row's position in the padded image is worked out once per LPT loads (one piece per thread where the
+    // rounding up to whole passes would cost the six-wavefront variant staging registers it does not have)
+    constexpr int CO = CT / 8, LPT = CO >= 16 ? 4 : (NT % 256 == 0 ? 2 : 1), TPR = CO / LPT, BRPP = NT / TPR,
+                  BNP = (PRF + BRPP - 1) / BRPP;
     constexpr int NG = BP / 16;                                  // 16-pixel MFMA groups per chunk
-    static_assert(BP % ARPP == 0 && NT % KO == 0 && NT % CO == 0, "tiles must split evenly over the threads");
+    static_assert(CO % LPT == 0 && NT % TPR == 0 && BP % ARPP == 0 && NT % KO == 0, "tiles must split evenly over the threads");
 
     __shared__ __attribute__((aligned(16))) uint16_t dzs[2][BP * PA];
     __shared__ __attribute__((aligned(16))) uint16_t panel[2][PRF * PB];
@@ -83,8 +87,8 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const Gemm
 
     const uint16_t *dzsrc = (const uint16_t *)p.a, *xsrc = (const uint16_t *)p.b, *mask = (const uint16_t *)p.mask;
     const int ako = tid % KO, arow0 = tid / KO;
-    const int bco = tid % CO, brow0 = tid / CO;
-    uint4 areg[ANP], breg[BNP];
+    const int bq = tid % TPR, brow0 = tid / TPR;
+    uint4 areg[ANP], breg[BNP][LPT];
     int tab_next = 0;
     const int pad_pix_total = g.N * p.Hp * Wp;
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
@@ -110,16 +114,21 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const Gemm
         }
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
-            const int row = brow0 + i * BRPP, idx = ps + row, c = c0 + bco * 8;
-            uint4 v = zero4;
-            if (row < nrows && idx < pad_pix_total && c < g.C) {
+            const int row = brow0 + i * BRPP, idx = ps + row;
+            const uint16_t *src = nullptr;
+            if (row < nrows && idx < pad_pix_total) {
                 const int n = p.dHpWp.div(idx), r2 = idx - n * p.Hp * Wp;
                 const int hp = p.dWp.div(r2), wp = r2 - hp * Wp;
                 const int h = hp - g.ph, w = wp - g.pw;
                 if ((unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
-                    v = *(const uint4 *)(xsrc + ((n * g.H + h) * g.W + w) * g.C + c);
+                    src = xsrc + ((size_t)(n * g.H + h) * g.W + w) * g.C + c0 + bq * 8;
             }
-            breg[i] = v;
+#pragma unroll
+            for (int j = 0; j < LPT; j++) {
+                uint4 v = zero4;
+                if (src && c0 + (bq + j * TPR) * 8 < g.C) v = *(const uint4 *)(src + j * TPR * 8);
+                breg[i][j] = v;
+            }
         }
         if (tid < BP) {
             const int pix = pix0 + tid;
@@ -133,7 +142,10 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const Gemm
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
             const int row = brow0 + i * BRPP;
-            if (row < PRF) *(uint4 *)(panel[buf] + row * PB + bco * 8) = breg[i];
+            if (row < PRF) {
+#pragma unroll
+                for (int j = 0; j < LPT; j++) *(uint4 *)(panel[buf] + row * PB + (bq + j * TPR) * 8) = breg[i][j];
+            }
         }
         if (tid < BP) prow_tab[buf][tid] = tab_next;
     };
