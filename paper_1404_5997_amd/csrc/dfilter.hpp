@@ -29,7 +29,10 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
     constexpr int NT = 64 * WK * WC, KT = 32 * WK, CT = 32 * WC, BP = 32;
     constexpr int PA = KT + 4, PB = CT + 4;
     constexpr int KQ = KT / 4, ARPP = NT / KQ, ANP = BP / ARPP;          // dz loader
-    constexpr int CQ = CT / 4, BRPP = NT / CQ, BNP = (PRF + BRPP - 1) / BRPP;   // x panel loader
+    // x panel loader: a thread fetches LPT 16-byte pieces of one panel row (pieces bq, bq + TPR, ...), so the
+    // row's position in the padded image is worked out once per LPT loads
+    constexpr int CQ = CT / 4, LPT = 4, TPR = CQ / LPT, BRPP = NT / TPR, BNP = (PRF + BRPP - 1) / BRPP;
+    static_assert(CQ % LPT == 0 && NT % TPR == 0, "panel rows must split evenly over the threads");
     static_assert(BP % ARPP == 0, "dz chunk must split evenly over the threads");
 
     __shared__ __attribute__((aligned(16))) float dzs[BP * PA];
@@ -63,8 +66,8 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
 
     const T *dzsrc = (const T *)p.a, *xsrc = (const T *)p.b, *mask = (const T *)p.mask;
     const int akq = tid % KQ, arow0 = tid / KQ;
-    const int bcq = tid % CQ, brow0 = tid / CQ;
-    float4 areg[ANP], breg[BNP];
+    const int bq = tid % TPR, brow0 = tid / TPR;
+    float4 areg[ANP], breg[BNP][LPT];
     int tab_next = 0;
     const int pad_pix_total = g.N * p.Hp * Wp;
 
@@ -102,16 +105,21 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
         }
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
-            const int row = brow0 + i * BRPP, idx = ps + row, c = c0 + bcq * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (row < nrows && idx < pad_pix_total && c < g.C) {
+            const int row = brow0 + i * BRPP, idx = ps + row;
+            int off = -1;
+            if (row < nrows && idx < pad_pix_total) {
                 const int n = p.dHpWp.div(idx), r2 = idx - n * p.Hp * Wp;
                 const int hp = p.dWp.div(r2), wp = r2 - hp * Wp;
                 const int h = hp - g.ph, w = wp - g.pw;
                 if ((unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
-                    v = load4(xsrc, ((n * g.H + h) * g.W + w) * g.C + c);
+                    off = ((n * g.H + h) * g.W + w) * g.C + c0 + bq * 4;
             }
-            breg[i] = v;
+#pragma unroll
+            for (int j = 0; j < LPT; j++) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (off >= 0 && c0 + (bq + j * TPR) * 4 < g.C) v = load4(xsrc, off + j * TPR * 4);
+                breg[i][j] = v;
+            }
         }
         if (tid < BP) {
             const int pix = pix0 + tid;
@@ -125,7 +133,10 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
             const int row = brow0 + i * BRPP;
-            if (row < PRF) *(float4 *)(panel + row * PB + bcq * 4) = breg[i];
+            if (row < PRF) {
+#pragma unroll
+                for (int j = 0; j < LPT; j++) *(float4 *)(panel + row * PB + (bq + j * TPR) * 4) = breg[i][j];
+            }
         }
         if (tid < BP) prow_tab[tid] = tab_next;
     };
