@@ -46,7 +46,12 @@ template <int WK, int WC, int KB, int TAPS, int PRF, int OCC>
 __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WK * WC, KT = 32 * KB * WK, CT = 32 * WC, BP = 64;
-    constexpr int PA = KT + 16, PB = CT + 16;                    // row pitches in elements: data + 32 bytes
+    // Row pitches in elements.  A transposing read touches 64 bytes of each of four consecutive rows per
+    // half-wave: with rows 64 bytes (mod 256) apart the four pieces fall on disjoint banks.  The two variants
+    // that run two work-groups per CU have no LDS to spare and keep a 32-byte pad (two-way conflicts).
+    constexpr int PAD = OCC >= 2 ? 16 : 32, PA = KT + PAD, PB = CT + PAD;
+    static_assert(OCC >= 2 || ((2 * PA) % 256 == 64 || (2 * PA) % 256 == 192), "dz rows must fall on disjoint banks");
+    static_assert(OCC >= 2 || ((2 * PB) % 256 == 64 || (2 * PB) % 256 == 192), "panel rows must fall on disjoint banks");
     constexpr int KO = KT / 8, ARPP = NT / KO, ANP = BP / ARPP;                  // dz loader (16-byte pieces)
     // x panel loader: a thread fetches LPT 16-byte pieces of one panel row (pieces bq, bq + TPR, ...), so the
     // row's position in the padded image is worked out once per LPT loads (one piece per thread where the
