@@ -185,17 +185,26 @@ def main():
 
     # HBM bytes per launch of that variant, from the committed counter summary (profiles/hbm_traffic.json:
     # FETCH_SIZE / WRITE_SIZE per dispatch, scaled by what a plain copy of known size reads), if it has them
-    traffic = None
+    traffic, traffic_kernel = None, None
     tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tpath):
         table_t = json.load(open(tpath)).get(args.workload, {})
         got = [table_t[k]["fetch_bytes"] + table_t[k]["write_bytes"] for k in dom["keys"] if k in table_t]
         if len(got) == len(dom["keys"]):
             traffic = round(sum(got) / len(got))
+        else:
+            # the tuner picked a variant the profiled run did not use: take the same calls as they were
+            # profiled (same layer passes, the kernel named in traffic_kernel)
+            ck = ["call " + c for c in dom["calls"]]
+            if all(k in table_t for k in ck):
+                traffic = round(sum(table_t[k]["fetch_bytes"] + table_t[k]["write_bytes"] for k in ck) / len(ck))
+                traffic_kernel = sorted(set(table_t[k].get("kernel", "?") for k in ck))
     roofline = {"bound": "mfma", "kernel": dom_name, "calls": dom["calls"],
                 "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
                 "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
                 "frac": round(achieved / PEAK_TFLOPS[dt], 4), "traffic": traffic}
+    if traffic_kernel:
+        roofline["traffic_kernel"] = traffic_kernel
 
     # the HBM-bound kernels of the step: algorithmic bytes (each operand once) over the measured duration
     esz = 2 if dt == "bf16" else 4

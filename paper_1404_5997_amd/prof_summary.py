@@ -119,13 +119,28 @@ def main():
         # the counter reads KiB; a plain copy of COPY_BYTES should read COPY_BYTES / 1024
         scale[which] = (COPY_BYTES / 1024.0) / (sum(vals) / len(vals)) if vals else 1.0
         agg = collections.OrderedDict()
+        names = {}
+        seen = {"fwd": 0, "bwd_filter": 0, "bwd_data": 0}
+        nlayers = sum(1 for d in body if (family(d["Kernel_Name"]) or "").endswith(" fwd")) // a.steps
         for d in body:
+            if is_step_start(d["Kernel_Name"]):
+                seen = {"fwd": 0, "bwd_filter": 0, "bwd_data": 0}
             fam = family(d["Kernel_Name"])
             if fam is None:
                 continue
             agg.setdefault("%s %d" % (fam, d["Grid_Size"]), []).append(d["c"][cname])
+            # the same dispatch under the name of the call it serves: forward runs conv1..convL, backward
+            # convL..conv1 (filter gradient, then data gradient), one convolution kernel per call
+            ps = fam.split()[1]
+            layer = seen[ps] + 1 if ps == "fwd" else nlayers - seen[ps]
+            seen[ps] += 1
+            ck = "call conv%d %s" % (layer, ps)
+            agg.setdefault(ck, []).append(d["c"][cname])
+            names[ck] = short(d["Kernel_Name"])
         for k, v in agg.items():
             traffic.setdefault(k, {})["%s_bytes" % which] = round(sum(v) / len(v) * 1024.0 * scale[which])
+            if k in names:
+                traffic[k]["kernel"] = names[k]
     if traffic:
         tpath = os.path.join(a.out, "hbm_traffic.json")
         allw = json.load(open(tpath)) if os.path.exists(tpath) else {}
