@@ -28,7 +28,7 @@ __device__ __forceinline__ uint32_t mask_pair(uint32_t v, uint32_t y)
 }
 
 template <class Epi, bool BWD, int WM, int WN, int PR>
-__global__ void __launch_bounds__(64 * WM * WN, 2) dconv_bf16_kernel(const GemmParams p)
+__global__ void __launch_bounds__(64 * WM * WN, (WM * WN >= 4 ? 2 : 1)) dconv_bf16_kernel(const GemmParams p)
 {
     constexpr int BK = 64, NT = 64 * WM * WN, BM = 64 * WM, BN = 64 * WN, PITCH = BK + 8;   // in bf16 elements
     constexpr int OCTS = BK / 8;                                 // 16-byte pieces per row

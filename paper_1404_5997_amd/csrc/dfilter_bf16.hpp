@@ -42,8 +42,9 @@ __device__ __forceinline__ short4_t lds_read_tr16(const uint16_t *p)
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4_t *)p);
 }
 
+// OCC = work-groups per CU; the second launch bound is wavefronts per SIMD.
 template <int WK, int WC, int KB, int TAPS, int PRF, int OCC>
-__global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter16_kernel(const GemmParams p)
+__global__ void __launch_bounds__(64 * WK * WC, (OCC * WK * WC >= 4 ? OCC * WK * WC / 4 : 1)) dfilter16_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WK * WC, KT = 32 * KB * WK, CT = 32 * WC, BP = 64;
     // Row pitches in elements.  A transposing read touches 64 bytes of each of four consecutive rows per
