@@ -14,12 +14,14 @@
 // points at four consecutive values (row s/4, columns 4*(s%4)..+3 of a 4 x 16 block), lane i
 // receives column i of rows 0..3.  Two such reads give a lane its 8 pixels of one channel.
 //
-// A wavefront holds KB x TAPS accumulators of 32 x 32, so one dz fragment feeds TAPS MFMAs and
-// one x fragment KB of them; a work-group handles one filter row (3 taps with KB = 4, or 5
-// taps with KB = 2: 192 / 160 accumulator registers, one wavefront per SIMD).  The LDS read
-// rate (two 8-byte transposing reads per fragment) is what bounds the kernel, not the MFMA
-// rate, so the register blocking is chosen for few reads per MFMA: (2 KB + 2 TAPS) reads per
-// KB x TAPS MFMAs.  LDS is double buffered: one barrier per 64-pixel chunk.
+// A wavefront holds KB x TAPS accumulators of 32 x 32 (filter blocks x the taps of one filter row), so one
+// dz fragment feeds TAPS MFMAs and one x fragment KB of them: (2 KB + 2 TAPS) transposing reads per
+// KB x TAPS MFMAs.  The host's variant table pairs each work-group tile with two splits of it: few
+// wavefronts with KB = 4 (or 2 for five taps; 192 / 160 accumulator registers, one wavefront per SIMD, fewest
+// LDS reads per MFMA), or twice / three times the wavefronts with half / a quarter of the filter blocks each.
+// The second kind is faster by 15-20 %: at the bf16 MFMA rate a wavefront's waits (fragments, the chunk
+// barrier, address arithmetic) are only filled by another wavefront on the same SIMD; sixteen wavefronts of
+// one block each lose again to the LDS read rate.  LDS is double buffered: one barrier per 64-pixel chunk.
 #pragma once
 #include "igemm.hpp"
 
