@@ -14,7 +14,7 @@ LIB = os.path.join(HERE, "libowt.so")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)
-FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function",
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-inline-asm",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
@@ -30,6 +30,7 @@ def _units():
                           ["-DOWT_INST_PASS=%d" % ps, "-DOWT_INST_BF16=%d" % bf]))
     for ps, pname in ((0, "fwd"), (1, "data")):
         units.append(("dconv16_%s.o" % pname, "dconv_bf16_inst.hip", ["-DOWT_INST_PASS=%d" % ps]))
+    units.append(("fcgemm.o", "fcgemm_inst.hip", []))
     units.append(("dfilter16.o", "dfilter_bf16_inst.hip", []))
     units.append(("sconv16.o", "sconv_bf16_inst.hip", []))
     units.append(("sfilter16.o", "sfilter_bf16_inst.hip", []))

@@ -57,7 +57,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -486,11 +486,40 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             }
         }
     }
+    // plain matrix product (the fully-connected shard), fp32 storage: the dense kernel with operands streamed
+    // straight into LDS; needs 16-byte aligned operand rows and, in the forward pass, whole 32-deep
+    // reduction steps (the backward passes can read a zero-padded copy of dz instead)
+    if (!no_direct && !g.bf16 && g.H == 1 && g.W == 1 && g.R == 1 && g.S == 1 &&
+        (pass == OWT_PASS_FWD ? dm.Kd % 32 == 0 : dm.Ncols % 4 == 0)) {
+        for (int t = 0; t < kNumFcTiles; t++) {
+            if (force_tile >= 0 && force_tile != 16 + t) continue;
+            const FcTile &ft = kFcTiles[t];
+            const long BM = 32 * ft.MB * ft.WM, BN = 32 * ft.NB * ft.WN;
+            const long steps = cdiv(dm.Kd, 32), tm = cdiv(dm.M, BM), tn = cdiv(dm.Ncols, BN);
+            for (long s0 : split_ladder(tm * tn, 256 * ft.occ)) {
+                long s = s0;
+                if (force_split > 0) s = force_split < steps ? force_split : steps;
+                if (force_split <= 0 && s > 1 && (steps / s < 2 || tm * tn * s > 2048)) break;
+                const long per = cdiv(steps, s), splits = cdiv(steps, per);
+                Launch l; memset(&l, 0, sizeof(l));
+                l.kind = KIND_FCGEMM; l.tile = t; l.splits = (int)splits; l.steps = (int)steps; l.steps_per_split = (int)per;
+                l.tiles_m = (int)tm; l.tiles_n = (int)tn;
+                if (splits > 1) l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                if (pass != OWT_PASS_FWD) l.pre_bytes = pad256((size_t)((g.N + 31) & ~31) * ((g.K + 31) & ~31) * 4);     // padded dz
+                l.cost = model_cost(tm * tn * splits, 4, ft.occ, (double)BM * BN * 32 * per, 1.6, splits, dm.M, dm.Ncols);
+                bool dup = l.partial_bytes > kMaxPartialBytes && force_split <= 0;
+                for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
+                if (!dup) out.push_back(l);
+                if (force_split > 0) break;
+            }
+        }
+    }
     // the gather kernel is the fallback of the stride-1 forward / backward-data kernel, and an
     // alternative worth timing next to the direct filter-gradient kernel
     const bool have_direct = !out.empty() && (out[0].kind == KIND_DIRECT || out[0].kind == KIND_DIRECT16);
     for (int t = 0; t < NUM_TILES && !have_direct; t++) {
         if (!vec && t != TILE_64x64) continue;
+        if (force_tile >= 16 && !out.empty()) continue;
         if (vec && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
         const TileInfo &ti = kTiles[t];
         const long ksteps = cdiv(dm.Kd, ti.BK);
@@ -558,7 +587,9 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
     p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.pre_bytes + l.partial_bytes) : nullptr;
     const bool bf = dt == OWT_BF16;
     hipError_t e;
-    if (l.kind == KIND_DIRECT16) {
+    if (l.kind == KIND_FCGEMM) {
+        e = owt_launch_fcgemm(pass, l.tile, p, (float *)ws, s);
+    } else if (l.kind == KIND_DIRECT16) {
         dconv_frame(g, pass, p);
         e = pass == OWT_PASS_FWD ? owt_launch_dconv16_fwd(l.tile, l.pr, p, s) : owt_launch_dconv16_data(l.tile, l.pr, p, ws, s);
     } else if (l.kind == KIND_SCONV16) {
@@ -615,6 +646,12 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     // figure profilers list as its grid size)
     static const char *pn[3] = {"fwd", "bwd_data", "bwd_filter"};
     const char *ds = dt == OWT_BF16 ? "bf16" : "f32";
+    if (l.kind == KIND_FCGEMM) {
+        const FcTile &ft = kFcTiles[l.tile];
+        return snprintf(buf, n, "fcgemm %s %s tile%dx%dx32 splitk%d grid%dx%d threads%ld", pn[pass], ds, 32 * ft.MB * ft.WM,
+                        32 * ft.NB * ft.WN, l.splits, l.tiles_m * l.tiles_n, l.splits,
+                        (long)l.tiles_m * l.tiles_n * l.splits * 64 * ft.WM * ft.WN);
+    }
     if (l.kind == KIND_SCONV16)
         return snprintf(buf, n, "sconv16 %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConv16TP, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConv16NT);

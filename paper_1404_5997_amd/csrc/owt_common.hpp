@@ -57,6 +57,9 @@ struct GemmParams {
     // `taps` at a time, either all R*S at once (groups == 1) or one filter row per group.
     int Hp, Wp, taps, groups, ctiles;
     FastDiv dWp, dHpWp;
+    // Dense kernel of the fully-connected shard only: row pitches of the A and B operands, and the true
+    // reduction length (the reduction runs over ksteps * 32 >= kvalid indices; A is zero beyond kvalid)
+    int lda, ldb, kvalid;
     // cpi > 0: the pixel chunks never straddle two images (cpi chunks per image, the last one short)
     int cpi;
     FastDiv dCpi;

@@ -71,6 +71,15 @@ constexpr DFilter16Variant kDFilter16Variants[kNumDFilter16Variants] = {
 constexpr int kDFilter16BP = 64;
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 
+// Dense GEMM kernel of the fully-connected shard (fcgemm_inst.hip; fp32 storage, reduction length a
+// multiple of 32): WM x WN wavefronts of MB x NB accumulator blocks of 32 x 32, occ work-groups per CU.
+// When the pass masks dy by y > 0 or wants the bias gradient, a small kernel first writes dz to `dz`
+// ([N][O_local] floats of workspace) and the bias gradient to its place.
+struct FcTile { int WM, WN, MB, NB, occ; };
+constexpr int kNumFcTiles = 4;
+constexpr FcTile kFcTiles[kNumFcTiles] = {{2, 2, 2, 2, 1}, {2, 2, 1, 2, 2}, {2, 2, 2, 1, 2}, {2, 2, 1, 1, 3}};
+hipError_t owt_launch_fcgemm(int pass, int tile, const GemmParams &, float *dz, hipStream_t);
+
 // bf16-MFMA small-channel strided forward kernel (sconv_bf16_inst.hip); w2 = K x KSLOTS bf16 values of workspace.
 struct SConv16Geom;
 hipError_t owt_launch_sconv16(const GemmParams &, const SConv16Geom &, int ktiles, int nwg, void *w2, hipStream_t);

@@ -354,6 +354,31 @@ def test_fc_shard_small_and_ragged():
     fc_parity(128, 4096, 4096, 8, True, dt="bf16", seed=5)
 
 
+@pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (2, 1), (3, 1), (0, 2), (1, 3), (2, 7), (3, 5)])
+def test_fc_dense_kernel(tile, split):
+    # The dense kernel of the shard (operands streamed straight into LDS), every tile shape, forced, with and
+    # without a split reduction: tiles ragged in both directions, 2 to 7 reduction steps, masked dy with bias
+    # gradient and accumulation, batch and column counts that are not multiples of 32 or 4 (the backward
+    # passes then read a zero-padded copy of dz), and shapes where some or all passes do not qualify (they gather).
+    m = owt()
+    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(16 + tile), str(split)
+    try:
+        for (N, I, O), ok, kw in [((160, 224, 96), (1, 1, 1), dict(relu=True)),
+                                  ((128, 256, 192), (1, 1, 1), dict(relu=False, alpha=0.5, beta=-0.25)),
+                                  ((100, 64, 40), (1, 1, 1), dict(relu=True)),
+                                  ((128, 96, 125), (1, 1, 1), dict(relu=False)),
+                                  ((37, 64, 125), (1, 1, 1), dict(relu=True, alpha=0.5, beta=0.5)),
+                                  ((96, 36, 64), (0, 1, 1), dict(relu=True, alpha=1.0 / 96, beta=1.0)),
+                                  ((64, 30, 32), (0, 0, 0), dict(relu=True))]:
+            d = m.conv_desc(N, I, 1, 1, O, 1, 1, 1, 0, m.OWT_F32, m.OWT_BIAS)
+            for ps in range(3):
+                assert ("fcgemm" in m.owt_conv_plan_describe(d, ps)) == bool(ok[ps]), (ps, m.owt_conv_plan_describe(d, ps))
+            fc_parity(N, I, O, 1, seed=900 + tile, **kw)
+    finally:
+        for k in ("OWT_TILE", "OWT_SPLITK"):
+            os.environ.pop(k, None)
+
+
 def test_fc_shard_bwd_without_dx_or_dbias():
     m = owt()
     g = np.random.default_rng(9)
