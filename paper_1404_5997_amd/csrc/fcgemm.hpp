@@ -8,8 +8,8 @@
 //
 // With a batch of 128 rows these products have few output tiles, so one work-group per CU has to hide
 // the memory latency by itself: the operand tiles of a 32-deep reduction step go from global memory
-// straight into LDS (global_load_lds, 16 bytes per lane, no register staging) into a ring of three
-// stages, two steps ahead of the MFMAs, with one bare s_barrier per step and explicit counter waits (a
+// straight into LDS (global_load_lds, 16 bytes per lane, no register staging) into a ring of NS
+// stages, NS - 1 steps ahead of the MFMAs, with one bare s_barrier per step and explicit counter waits (a
 // __syncthreads() would wait for the loads in flight as well).  The load is written as inline assembly:
 // the compiler keeps its own books on direct-to-LDS loads issued through the builtin and, with several
 // stages in flight, puts a wait for all of them in front of the LDS reads of the stage that has landed.
@@ -34,23 +34,22 @@
 
 namespace owt {
 
-template <bool AKM, bool BKM, class Epi, int WM, int WN, int MB, int NB, int OCC>
-__global__ void __launch_bounds__(64 * WM * WN, (OCC * WM * WN + 3) / 4) fcgemm_kernel(const GemmParams p)
+// One output tile (`tile` = tm * tiles_n + tn) over the reduction steps of `split`; lds holds NS stages.
+template <bool AKM, bool BKM, class Epi, int WM, int WN, int MB, int NB, int NS>
+__device__ __forceinline__ void fcgemm_tile(const GemmParams &p, int tile, int split, float *lds)
 {
     constexpr int NW = WM * WN, BM = 32 * MB * WM, BN = 32 * NB * WN, BK = 32;
     constexpr int AI = BM / 8 / NW, BI = BN / 8 / NW;      // direct-to-LDS loads per lane and stage (1 KB per wavefront each)
     constexpr int L = AI + BI;
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "every wavefront issues the same number of loads");
-    static_assert(L <= 15, "the wait below encodes its count in four bits");
+    static_assert(NS >= 3 && NS <= 5 && (NS - 2) * L <= 63, "the wait counter has six bits");
     constexpr int STAGE = (BM + BN) * BK;                  // floats: the A tile, then the B tile
-    __shared__ __attribute__((aligned(16))) float lds[3 * STAGE];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int li = lane & 31, lh = lane >> 5;
     const int wm0 = (wave / WN) * 32 * MB, wn0 = (wave % WN) * 32 * NB;
-    const int tm = blockIdx.x / p.tiles_n, tn = blockIdx.x - tm * p.tiles_n;
+    const int tm = tile / p.tiles_n, tn = tile - tm * p.tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
-    const int split = blockIdx.y;
     const int ks_beg = split * p.ksteps_per_split;
     const int nst = min(p.ksteps, ks_beg + p.ksteps_per_split) - ks_beg;
 
@@ -160,23 +159,29 @@ __global__ void __launch_bounds__(64 * WM * WN, (OCC * WM * WN + 3) / 4) fcgemm_
         }
     };
 
-    // s_waitcnt immediates: vmcnt(n), lgkmcnt(0), expcnt untouched
-    constexpr int kWaitOneAhead = (L & 15) | (7 << 4), kWaitAll = 7 << 4;
-    issue(ks_beg, 0);
-    if (nst > 1) issue(ks_beg + 1, 1);
-    int cur = 0;                               // stage s lives in buffer s % 3
+    // s_waitcnt vmcnt(n) lgkmcnt(0), expcnt untouched; n = this lane's loads of the stages that may stay in flight
+#define OWT_WAIT_STAGES(k) __builtin_amdgcn_s_waitcnt((((k) * L) & 15) | ((((k) * L) >> 4) << 14) | (7 << 4))
+#pragma unroll
+    for (int i = 0; i < NS - 1; i++)
+        if (i < nst) issue(ks_beg + i, i);
+    int cur = 0, fill = NS - 1;                // stage s lives in buffer s % NS; `fill` is the buffer of stage s + NS - 1
     for (int s = 0; s < nst; s++) {
-        // this lane's pieces of stage s have landed (stage s + 1 may still be in flight) and its LDS reads of
-        // stage s - 1 are done; after the barrier that holds for the whole work-group, so stage s can be read
-        // and the buffer of stage s - 1 refilled
-        if (s + 1 < nst) __builtin_amdgcn_s_waitcnt(kWaitOneAhead);
-        else __builtin_amdgcn_s_waitcnt(kWaitAll);
+        // this lane's pieces of stage s have landed (up to NS - 2 later stages may still be in flight) and its
+        // LDS reads of stage s - 1 are done; after the barrier that holds for the whole work-group, so stage s
+        // can be read and the buffer of stage s - 1 refilled
+        const int ahead = min(NS - 2, nst - 1 - s);
+        if (ahead == 0) OWT_WAIT_STAGES(0);
+        else if (ahead == 1) OWT_WAIT_STAGES(1);
+        else if (ahead == 2) OWT_WAIT_STAGES(NS >= 4 ? 2 : 1);
+        else OWT_WAIT_STAGES(NS >= 5 ? 3 : 1);
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");         // no LDS read of stage s moves above the barrier
-        if (s + 2 < nst) issue(ks_beg + s + 2, cur == 0 ? 2 : cur - 1);
+        if (s + NS - 1 < nst) issue(ks_beg + s + NS - 1, fill);
         compute(lds + cur * STAGE, lds + cur * STAGE + BM * BK);
-        cur = cur == 2 ? 0 : cur + 1;
+        cur = cur == NS - 1 ? 0 : cur + 1;
+        fill = fill == NS - 1 ? 0 : fill + 1;
     }
+#undef OWT_WAIT_STAGES
 
     // accumulator register r of lane (li, lh): row 8*(r/4) + 4*lh + r%4, column li of its 32 x 32 block
     typedef typename Epi::TOut TOut;
@@ -198,6 +203,25 @@ __global__ void __launch_bounds__(64 * WM * WN, (OCC * WM * WN + 3) / 4) fcgemm_
                 else store1(out, o, Epi::op(p, row, col, acc[bm][bn][r]));
             }
         }
+}
+
+template <bool AKM, bool BKM, class Epi, int WM, int WN, int MB, int NB, int NS, int OCC>
+__global__ void __launch_bounds__(64 * WM * WN, (OCC * WM * WN + 3) / 4) fcgemm_kernel(const GemmParams p)
+{
+    __shared__ __attribute__((aligned(16))) float lds[NS * 32 * (MB * WM + NB * WN) * 32];
+    fcgemm_tile<AKM, BKM, Epi, WM, WN, MB, NB, NS>(p, blockIdx.x, blockIdx.y, lds);
+}
+
+// Both backward products of a shard in one launch (neither split): the first tiles_m * tiles_n work-groups
+// of pd's grid compute dx, the rest dw.  Each product alone leaves CUs idle in its last round of
+// work-groups; together the long dx tiles start first and the short dw tiles fill the gaps.
+template <int WM, int WN, int MB, int NB, int NS, int OCC>
+__global__ void __launch_bounds__(64 * WM * WN, (OCC * WM * WN + 3) / 4) fcgemm_bwd_pair_kernel(const GemmParams pd, const GemmParams pf)
+{
+    __shared__ __attribute__((aligned(16))) float lds[NS * 32 * (MB * WM + NB * WN) * 32];
+    const int nd = pd.tiles_m * pd.tiles_n;
+    if ((int)blockIdx.x < nd) fcgemm_tile<true, false, EpiData<float>, WM, WN, MB, NB, NS>(pd, blockIdx.x, 0, lds);
+    else fcgemm_tile<false, false, EpiFilter, WM, WN, MB, NB, NS>(pf, blockIdx.x - nd, 0, lds);
 }
 
 // dz = dy where y > 0, else 0 (when y is given), written as an [Np][Op] array whose rows past N and columns

@@ -577,14 +577,20 @@ static size_t max_workspace(const Geom &g, int pass, const PassDims &dm, bool wa
     return m;
 }
 
-static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, GemmParams p, const Launch &l,
-                         void *ws, hipStream_t s)
+// The part of the kernel parameters that the chosen launch decides.
+static void frame_params(const Geom &g, const PassDims &dm, const Launch &l, void *ws, GemmParams &p)
 {
     p.g = g; p.M = (int)dm.M; p.Ncols = (int)dm.Ncols; p.Kd = (int)dm.Kd;
     p.splits = l.splits; p.ksteps = l.steps; p.ksteps_per_split = l.steps_per_split;
     p.tiles_m = l.tiles_m; p.tiles_n = l.tiles_n;
     p.partial = l.splits > 1 ? (float *)((char *)ws + l.pre_bytes) : nullptr;
     p.dbias_partial = (l.splits > 1 && l.dbias_bytes) ? (float *)((char *)ws + l.pre_bytes + l.partial_bytes) : nullptr;
+}
+
+static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, GemmParams p, const Launch &l,
+                         void *ws, hipStream_t s)
+{
+    frame_params(g, dm, l, ws, p);
     const bool bf = dt == OWT_BF16;
     hipError_t e;
     if (l.kind == KIND_FCGEMM) {
@@ -760,6 +766,49 @@ static GemmParams filter_params(const owt_conv_desc *d, const void *x, const voi
     p.a = dy; p.b = x; p.out = dw; p.flags = d->flags; p.alpha = alpha; p.beta = beta; p.dbias = db;
     p.mask = (d->flags & OWT_RELU) ? y : nullptr;
     return p;
+}
+
+// Backward pass of a fully-connected shard when both of its products run on the dense kernel.
+struct FcPair { Launch ld, lf; bool fused; };
+static std::map<PlanKey, int> g_fc_fused;      // timed by owt_fc_autotune: 1 = one launch for both products
+
+static bool find_fc_launch(const Geom &g, int pass, int tile, Launch &out)
+{
+    std::vector<Launch> c;
+    enumerate(g, pass, conv_dims(g, pass), pass == OWT_PASS_BWD_FILTER, c);
+    for (const Launch &l : c)
+        if (l.kind == KIND_FCGEMM && l.tile == tile && l.splits == 1) { out = l; return true; }
+    return false;
+}
+
+static bool fc_pair_plan(const Geom &g, owt_dtype dt, FcPair &fp)
+{
+    fp.ld = choose(g, OWT_PASS_BWD_DATA, dt, conv_dims(g, OWT_PASS_BWD_DATA), false, true);
+    fp.lf = choose(g, OWT_PASS_BWD_FILTER, dt, conv_dims(g, OWT_PASS_BWD_FILTER), true, true);
+    if (fp.ld.kind != KIND_FCGEMM || fp.lf.kind != KIND_FCGEMM) return false;
+    fp.fused = false;
+    Launch fd, ff;
+    if (getenv("OWT_FC_TWO_LAUNCHES") || !find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) ||
+        !find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff))
+        return true;
+    int fused = 1;                               // untimed: one launch
+    {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        auto it = g_fc_fused.find(plan_key(g, 3, dt));
+        if (it != g_fc_fused.end()) fused = it->second;
+    }
+    if (getenv("OWT_FC_ONE_LAUNCH")) fused = 1;
+    if (fused) { fp.ld = fd; fp.lf = ff; fp.fused = true; }
+    return true;
+}
+
+static owt_status launch_fc_pair(const Geom &g, const FcPair &fp, GemmParams pd, GemmParams pf, void *ws, hipStream_t s)
+{
+    frame_params(g, conv_dims(g, OWT_PASS_BWD_DATA), fp.ld, ws, pd);
+    frame_params(g, conv_dims(g, OWT_PASS_BWD_FILTER), fp.lf, ws, pf);
+    const hipError_t e = owt_launch_fcgemm_bwd(fp.ld.tile, fp.lf.tile, fp.fused, pd, pf, (float *)ws, s);
+    if (e != hipSuccess) return fail(OWT_ELAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
+    return OWT_OK;
 }
 
 }  // namespace owt
@@ -984,14 +1033,20 @@ owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, 
     if (ws_bytes < need) return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
     if (need && (!ws || !aligned16(ws))) return fail(OWT_EINVAL, "ws is NULL or misaligned");
     const void *mask = (d->flags & OWT_RELU) ? y_or_null : nullptr;
-    if (dx_partial_or_null) {
-        GemmParams p; memset(&p, 0, sizeof(p));
-        p.a = dy; p.b = w; p.out = dx_partial_or_null; p.flags = d->flags; p.mask = mask;
-        OWT_TRY(conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, p, false, ws, ws_bytes, (hipStream_t)hip_stream, true));
-    }
+    GemmParams pd; memset(&pd, 0, sizeof(pd));
+    pd.a = dy; pd.b = w; pd.out = dx_partial_or_null; pd.flags = d->flags; pd.mask = mask;
     GemmParams p; memset(&p, 0, sizeof(p));
     p.a = dy; p.b = x; p.out = dw; p.flags = d->flags; p.alpha = alpha; p.beta = beta;
     p.dbias = dbias_or_null; p.mask = mask;
+    if (dx_partial_or_null) {
+        // both products on the dense kernel: one dz for the two, and one launch for both when that is faster
+        FcPair fp;
+        if (fc_pair_plan(g, d->dtype, fp)) {
+            OWT_TRY(check_ws(fp.ld, ws, ws_bytes)); OWT_TRY(check_ws(fp.lf, ws, ws_bytes));
+            return launch_fc_pair(g, fp, pd, p, ws, (hipStream_t)hip_stream);
+        }
+        OWT_TRY(conv_pass(g, OWT_PASS_BWD_DATA, d->dtype, pd, false, ws, ws_bytes, (hipStream_t)hip_stream, true));
+    }
     return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, p, true, ws, ws_bytes, (hipStream_t)hip_stream, true);
 }
 
@@ -1012,8 +1067,44 @@ owt_status owt_fc_autotune(const owt_fc_desc *d, const void *x, const void *w, c
     OWT_TRY(owt_conv_autotune(&c, OWT_PASS_FWD, x, w, bias, y, nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, hip_stream));
     OWT_TRY(owt_conv_autotune(&c, OWT_PASS_BWD_DATA, nullptr, w, nullptr, y, dy, dx_partial, nullptr, nullptr, ws, ws_bytes,
                               hip_stream));
-    return owt_conv_autotune(&c, OWT_PASS_BWD_FILTER, x, w, nullptr, y, dy, nullptr, dw, dbias_or_null, ws, ws_bytes,
-                             hip_stream);
+    OWT_TRY(owt_conv_autotune(&c, OWT_PASS_BWD_FILTER, x, w, nullptr, y, dy, nullptr, dw, dbias_or_null, ws, ws_bytes,
+                              hip_stream));
+    // both backward products on the dense kernel: two launches (the tiles just timed) or one for both?
+    Launch fd, ff;
+    if (env_overrides() || !find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) || !find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff))
+        return OWT_OK;
+    FcPair two;
+    two.ld = choose(g, OWT_PASS_BWD_DATA, d->dtype, conv_dims(g, OWT_PASS_BWD_DATA), false, true);
+    two.lf = choose(g, OWT_PASS_BWD_FILTER, d->dtype, conv_dims(g, OWT_PASS_BWD_FILTER), true, true);
+    two.fused = false;
+    if (two.ld.kind != KIND_FCGEMM || two.lf.kind != KIND_FCGEMM) return OWT_OK;
+    FcPair one; one.ld = fd; one.lf = ff; one.fused = true;
+    const void *mask = (d->flags & OWT_RELU) ? y : nullptr;
+    GemmParams pd; memset(&pd, 0, sizeof(pd));
+    pd.a = dy; pd.b = w; pd.out = dx_partial; pd.flags = d->flags; pd.mask = mask;
+    GemmParams pf; memset(&pf, 0, sizeof(pf));
+    pf.a = dy; pf.b = x; pf.out = dw; pf.flags = d->flags; pf.alpha = 1.f; pf.beta = 0.f; pf.dbias = dbias_or_null; pf.mask = mask;
+    hipStream_t s = (hipStream_t)hip_stream;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return fail(OWT_ELAUNCH, "hipEventCreate failed");
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return fail(OWT_ELAUNCH, "hipEventCreate failed"); }
+    float ms[2] = {0.f, 0.f};
+    owt_status st = OWT_OK;
+    for (int v = 0; v < 2 && st == OWT_OK; v++) {
+        const FcPair &fp = v ? one : two;
+        st = launch_fc_pair(g, fp, pd, pf, ws, s);                                 // warm-up
+        bool ok = st == OWT_OK && hipEventRecord(e0, s) == hipSuccess;
+        for (int r = 0; r < 3 && st == OWT_OK; r++) st = launch_fc_pair(g, fp, pd, pf, ws, s);
+        if (st != OWT_OK) break;
+        ok = ok && hipEventRecord(e1, s) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+             hipEventElapsedTime(&ms[v], e0, e1) == hipSuccess;
+        if (!ok) st = fail(OWT_ELAUNCH, "timing the backward pair failed: %s", hipGetErrorString(hipGetLastError()));
+    }
+    (void)hipEventDestroy(e0); (void)hipEventDestroy(e1);
+    if (st != OWT_OK) return st;
+    std::lock_guard<std::mutex> lk(g_tuned_mutex);
+    g_fc_fused[plan_key(g, 3, d->dtype)] = ms[1] < ms[0] ? 1 : 0;
+    return OWT_OK;
 }
 
 }  // extern "C"

@@ -75,10 +75,16 @@ hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 // multiple of 32): WM x WN wavefronts of MB x NB accumulator blocks of 32 x 32, occ work-groups per CU.
 // When the pass masks dy by y > 0 or wants the bias gradient, a small kernel first writes dz to `dz`
 // ([N][O_local] floats of workspace) and the bias gradient to its place.
-struct FcTile { int WM, WN, MB, NB, occ; };
+// NS = stages of the LDS ring ((BM + BN) * 128 bytes each).
+struct FcTile { int WM, WN, MB, NB, NS, occ; };
 constexpr int kNumFcTiles = 4;
-constexpr FcTile kFcTiles[kNumFcTiles] = {{2, 2, 2, 2, 1}, {2, 2, 1, 2, 2}, {2, 2, 2, 1, 2}, {2, 2, 1, 1, 3}};
+constexpr FcTile kFcTiles[kNumFcTiles] = {{2, 2, 2, 2, 3, 1}, {2, 2, 1, 2, 3, 2}, {2, 2, 2, 1, 3, 2}, {2, 2, 1, 1, 3, 3}};
+constexpr int kFcPairTile = 3;      // the tile of the launch that runs both backward products
 hipError_t owt_launch_fcgemm(int pass, int tile, const GemmParams &, float *dz, hipStream_t);
+// Both backward products on one dz (data pass params first): two launches, or one when `fused`
+// (both with tile kFcPairTile, neither split).
+hipError_t owt_launch_fcgemm_bwd(int tile_d, int tile_f, bool fused, const GemmParams &pd, const GemmParams &pf, float *dz,
+                                 hipStream_t);
 
 // bf16-MFMA small-channel strided forward kernel (sconv_bf16_inst.hip); w2 = K x KSLOTS bf16 values of workspace.
 struct SConv16Geom;

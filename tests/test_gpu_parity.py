@@ -379,6 +379,28 @@ def test_fc_dense_kernel(tile, split):
             os.environ.pop(k, None)
 
 
+@pytest.mark.parametrize("mode", ["OWT_FC_ONE_LAUNCH", "OWT_FC_TWO_LAUNCHES", "tuned"])
+def test_fc_backward_pair(mode):
+    # Both backward products of a shard on the dense kernel share one dz; they run as one launch or as two.
+    # Forced either way, and chosen by owt_fc_autotune (whose timing runs must leave results unchanged).
+    m = owt()
+    if mode != "tuned":
+        os.environ[mode] = "1"
+    try:
+        for (N, I, O), kw in [((128, 512, 125), dict(relu=False)), ((96, 260, 192), dict(relu=True, alpha=0.25, beta=1.0)),
+                              ((33, 64, 40), dict(relu=True))]:
+            if mode == "tuned":
+                d = m.fc_desc(N, I, O, 1, 0, m.OWT_F32, m.OWT_BIAS | (m.OWT_RELU if kw["relu"] else 0))
+                g = np.random.default_rng(5)
+                t = lambda *sh: to_dev(g.standard_normal(sh, dtype=np.float32))
+                wsb = max(m.owt_fc_workspace_bytes(d, 0), m.owt_fc_workspace_bytes(d, 1))
+                m.owt_fc_autotune(d, t(N, I), t(O, I), t(O), t(N, O), t(N, O), empty((N, I), "f32"), empty((O, I), "f32"),
+                                  empty((O,), "f32"), workspace(wsb))
+            fc_parity(N, I, O, 1, seed=950, **kw)
+    finally:
+        os.environ.pop(mode, None)
+
+
 def test_fc_shard_bwd_without_dx_or_dbias():
     m = owt()
     g = np.random.default_rng(9)
