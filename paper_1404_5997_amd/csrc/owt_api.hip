@@ -548,12 +548,17 @@ static bool env_overrides()
            getenv("OWT_NO_BF16_MFMA");
 }
 
+static std::map<PlanKey, Launch> g_modelled;   // the cost model's choice per geometry (untimed), so that a call plans once
+
 static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, bool want_db, bool use_cache)
 {
-    if (use_cache && !env_overrides()) {
+    const bool cached = use_cache && !env_overrides();
+    if (cached) {
         std::lock_guard<std::mutex> lk(g_tuned_mutex);
         auto it = g_tuned.find(plan_key(g, pass, dt));
         if (it != g_tuned.end()) return it->second;
+        it = g_modelled.find(plan_key(g, pass, dt));
+        if (it != g_modelled.end()) return it->second;
     }
     std::vector<Launch> c;
     enumerate(g, pass, dm, want_db, c);
@@ -563,6 +568,10 @@ static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, 
     for (size_t i = 0; i < c.size(); i++) {
         if (only_direct && any_direct && c[i].kind == KIND_GATHER) continue;
         if (best == c.size() || c[i].cost < c[best].cost) best = i;
+    }
+    if (cached) {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        g_modelled[plan_key(g, pass, dt)] = c[best];
     }
     return c[best];
 }
@@ -781,25 +790,40 @@ static bool find_fc_launch(const Geom &g, int pass, int tile, Launch &out)
     return false;
 }
 
+static std::map<PlanKey, std::pair<bool, FcPair>> g_fc_pairs;     // planned once per geometry; owt_fc_autotune erases its entry
+
 static bool fc_pair_plan(const Geom &g, owt_dtype dt, FcPair &fp)
 {
+    const bool cached = !env_overrides() && !getenv("OWT_FC_TWO_LAUNCHES") && !getenv("OWT_FC_ONE_LAUNCH");
+    if (cached) {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        auto it = g_fc_pairs.find(plan_key(g, 3, dt));
+        if (it != g_fc_pairs.end()) { fp = it->second.second; return it->second.first; }
+    }
+    bool ok = false;
+    fp.fused = false;
     fp.ld = choose(g, OWT_PASS_BWD_DATA, dt, conv_dims(g, OWT_PASS_BWD_DATA), false, true);
     fp.lf = choose(g, OWT_PASS_BWD_FILTER, dt, conv_dims(g, OWT_PASS_BWD_FILTER), true, true);
-    if (fp.ld.kind != KIND_FCGEMM || fp.lf.kind != KIND_FCGEMM) return false;
-    fp.fused = false;
-    Launch fd, ff;
-    if (getenv("OWT_FC_TWO_LAUNCHES") || !find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) ||
-        !find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff))
-        return true;
-    int fused = 1;                               // untimed: one launch
-    {
-        std::lock_guard<std::mutex> lk(g_tuned_mutex);
-        auto it = g_fc_fused.find(plan_key(g, 3, dt));
-        if (it != g_fc_fused.end()) fused = it->second;
+    if (fp.ld.kind == KIND_FCGEMM && fp.lf.kind == KIND_FCGEMM) {
+        ok = true;
+        Launch fd, ff;
+        if (!getenv("OWT_FC_TWO_LAUNCHES") && find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) &&
+            find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff)) {
+            int fused = 1;                       // untimed: one launch
+            {
+                std::lock_guard<std::mutex> lk(g_tuned_mutex);
+                auto it = g_fc_fused.find(plan_key(g, 3, dt));
+                if (it != g_fc_fused.end()) fused = it->second;
+            }
+            if (getenv("OWT_FC_ONE_LAUNCH")) fused = 1;
+            if (fused) { fp.ld = fd; fp.lf = ff; fp.fused = true; }
+        }
     }
-    if (getenv("OWT_FC_ONE_LAUNCH")) fused = 1;
-    if (fused) { fp.ld = fd; fp.lf = ff; fp.fused = true; }
-    return true;
+    if (cached) {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        g_fc_pairs[plan_key(g, 3, dt)] = std::make_pair(ok, fp);
+    }
+    return ok;
 }
 
 static owt_status launch_fc_pair(const Geom &g, const FcPair &fp, GemmParams pd, GemmParams pf, void *ws, hipStream_t s)
@@ -972,6 +996,7 @@ owt_status owt_conv_autotune(const owt_conv_desc *d, int pass, const void *x, co
     if (st != OWT_OK) return st;
     std::lock_guard<std::mutex> lk(g_tuned_mutex);
     g_tuned[plan_key(g, pass, d->dtype)] = c[best];
+    g_fc_pairs.erase(plan_key(g, 3, d->dtype));      // a pair plan built on the old choice is stale
     return OWT_OK;
 }
 
@@ -1104,6 +1129,7 @@ owt_status owt_fc_autotune(const owt_fc_desc *d, const void *x, const void *w, c
     if (st != OWT_OK) return st;
     std::lock_guard<std::mutex> lk(g_tuned_mutex);
     g_fc_fused[plan_key(g, 3, d->dtype)] = ms[1] < ms[0] ? 1 : 0;
+    g_fc_pairs.erase(plan_key(g, 3, d->dtype));
     return OWT_OK;
 }
 
