@@ -226,26 +226,28 @@ __global__ void __launch_bounds__(64 * WM * WN, (OCC * WM * WN + 3) / 4) fcgemm_
 
 // dz = dy where y > 0, else 0 (when y is given), written as an [Np][Op] array whose rows past N and columns
 // past O are zero (when dz is given), and the bias gradient alpha * (column sums of dz) + beta * dbias (when
-// dbias is given): 32 columns x 8 row phases per work-group, the phases added in a fixed order.
+// dbias is given): 16 columns x 16 row phases per work-group, the phases added in a fixed order.  The whole
+// array is a few hundred KB, so the kernel is one round trip to memory long: every thread has its (up to 8)
+// rows in flight at once, and narrow column strips make enough work-groups for that.
 __global__ void __launch_bounds__(256) fc_dz_kernel(const float *__restrict__ dy, const float *__restrict__ y,
                                                     float *__restrict__ dz, float *dbias, float alpha, float beta, int N, int O,
                                                     int Np, int Op)
 {
-    __shared__ float red[8][32];
-    const int cl = threadIdx.x & 31, ph = threadIdx.x >> 5, c = blockIdx.x * 32 + cl;
+    __shared__ float red[16][16];
+    const int cl = threadIdx.x & 15, ph = threadIdx.x >> 4, c = blockIdx.x * 16 + cl;
     float s = 0.f;
-    for (int n0 = ph; n0 < Np; n0 += 64) {          // eight rows per round, their loads in flight together
+    for (int n0 = ph; n0 < Np; n0 += 128) {
         float v[8], m[8];
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const int n = n0 + 8 * j;
+            const int n = n0 + 16 * j;
             const bool in = n < N && c < O;
             v[j] = in ? dy[(size_t)n * O + c] : 0.f;
             m[j] = (in && y) ? y[(size_t)n * O + c] : 1.f;
         }
 #pragma unroll
         for (int j = 0; j < 8; j++) {
-            const int n = n0 + 8 * j;
+            const int n = n0 + 16 * j;
             const float t = m[j] > 0.f ? v[j] : 0.f;
             if (dz && n < Np && c < Op) dz[(size_t)n * Op + c] = t;
             s += t;
@@ -256,7 +258,7 @@ __global__ void __launch_bounds__(256) fc_dz_kernel(const float *__restrict__ dy
     if (ph == 0 && c < O && dbias) {
         float t = red[0][cl];
 #pragma unroll
-        for (int j = 1; j < 8; j++) t += red[j][cl];
+        for (int j = 1; j < 16; j++) t += red[j][cl];
         dbias[c] = alpha * t + (beta != 0.f ? beta * dbias[c] : 0.f);
     }
 }

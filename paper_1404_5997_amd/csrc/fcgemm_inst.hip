@@ -52,7 +52,7 @@ static hipError_t prepare_dz(int pass, GemmParams &p, float *dz, float *dbias, h
     const bool copy = p.mask || N % 32 || O % 32;
     const int Np = (N + 31) & ~31, Op = (O + 31) & ~31;
     if (copy || dbias) {
-        hipLaunchKernelGGL(fc_dz_kernel, dim3(Op / 32), dim3(256), 0, s, (const float *)p.a, (const float *)p.mask,
+        hipLaunchKernelGGL(fc_dz_kernel, dim3(Op / 16), dim3(256), 0, s, (const float *)p.a, (const float *)p.mask,
                            copy ? dz : nullptr, dbias, p.alpha, p.beta, N, O, Np, Op);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
