@@ -152,7 +152,10 @@ owt_status owt_fc_shard_fwd(const owt_fc_desc *d, const void *x, const void *w, 
  *   dx_partial[n,i] = sum_o dz[n,o] * w[o,i]     this worker's addend of the sum over workers;
  *                                                skipped when dx_partial_or_null is NULL
  *   dw[o,i] = alpha * sum_n dz[n,o] * x[n,i] + beta * dw;   dbias[o] likewise (NULL to skip)
- * dy, y [N,O_local]; dx_partial [N,I]; dw [O_local,I] fp32; dbias [O_local] fp32. */
+ * dy, y [N,O_local]; dx_partial [N,I]; dw [O_local,I] fp32; dbias [O_local] fp32.
+ * ws (owt_fc_workspace_bytes of pass OWT_PASS_BWD_DATA; that figure covers both
+ * products) holds a masked, zero-padded copy of dz and the partial sums of a split
+ * reduction while the call runs. */
 owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, const void *y_or_null,
                             const void *dy, float alpha, float beta, void *dx_partial_or_null,
                             float *dw, float *dbias_or_null, void *ws, size_t ws_bytes,
@@ -160,7 +163,8 @@ owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, 
 
 /* Optional tuning of a dense shard, as owt_conv_autotune does for a convolution:
  * times every kernel variant of the three passes (forward; the two halves of
- * owt_fc_shard_bwd) on the caller's buffers and remembers the fastest for later
+ * owt_fc_shard_bwd, and whether those two run faster as one launch or as two)
+ * on the caller's buffers and remembers the fastest for later
  * owt_fc_shard_* calls with an identical descriptor in this process.  Reads x,
  * w, bias, y (ReLU mask), dy; writes y, dx_partial, dw, dbias (alpha 1, beta 0).
  * All of these are required except dbias.  ws must hold the larger of the two
