@@ -221,14 +221,17 @@ static bool sconv_geom(const Geom &g, SConvGeom &sg)
     sg.SLOTS = (sg.SEG + sg.LPAD + 3) & ~3;
     const int a = g.pw * g.C + sg.LPAD + g.W * g.C, b = (g.Q - 1) * g.sw * g.C + sg.SLOTS;
     sg.PITCH = ((a > b ? a : b) + 3) & ~3;
-    sg.ROWS = (kSConvTP - 1) * g.sh + g.R;
+    // output rows that kSConvBand consecutive pixels can touch, and the input rows under them
+    int orows = (g.Q + kSConvBand - 2) / g.Q + 1;
+    if (orows > g.P) orows = g.P;
+    sg.ROWS = (orows - 1) * g.sh + g.R;
     sg.KSTEPS = (g.R * sg.SLOTS + kSConvBK - 1) / kSConvBK;
     sg.KSLOTS = sg.KSTEPS * kSConvBK;
-    sg.MPIX = kSConvTP * g.Q;
-    sg.units_per_image = (g.P + kSConvTP - 1) / kSConvTP;
+    sg.MPIX = kSConvBand;
+    sg.units_per_image = (g.P * g.Q + kSConvBand - 1) / kSConvBand;
     sg.units = g.N * sg.units_per_image;
     // the padded tail of the reduction runs past filter row R-1: those panel rows exist and stay zero
-    const int zr = (kSConvTP - 1) * g.sh + (sg.KSLOTS - 1) / sg.SLOTS + 1;
+    const int zr = (orows - 1) * g.sh + (sg.KSLOTS - 1) / sg.SLOTS + 1;
     sg.ZROWS = zr > sg.ROWS + 1 ? zr : sg.ROWS + 1;
     const size_t lds = ((size_t)2 * 64 * (kSConvBK + 4) + (size_t)sg.ZROWS * sg.PITCH) * 4;
     return sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 && sg.SLOTS >= 8 &&
@@ -350,7 +353,8 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             l.kind = KIND_SCONV; l.splits = 1; l.steps = scg.units; l.steps_per_split = (int)per;
             l.tiles_m = (int)ktiles; l.tiles_n = (int)n;
             l.partial_bytes = pad256((size_t)g.K * scg.KSLOTS * 4);          // the re-laid-out filters
-            l.cost = model_cost(ktiles * n, 8, 1, 256.0 * 64 * scg.KSLOTS * per, 1.0, 1, dm.M, dm.Ncols);
+            // (bf16 storage: the bf16-MFMA kernel below, when it applies, is the faster one)
+            l.cost = model_cost(ktiles * n, 8, 1, 256.0 * 64 * scg.KSLOTS * per, 1.0, 1, dm.M, dm.Ncols) * (g.bf16 ? 2.0 : 1.0);
             bool dup = false;
             for (const Launch &o : out) dup |= o.kind == l.kind && o.tiles_n == l.tiles_n;
             if (!dup) out.push_back(l);
@@ -671,7 +675,7 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
         return snprintf(buf, n, "sconv16 %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConv16TP, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConv16NT);
     if (l.kind == KIND_SCONV)
-        return snprintf(buf, n, "sconv %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConvTP, l.tiles_m, l.tiles_n,
+        return snprintf(buf, n, "sconv %s %s band%d grid%dx%d threads%ld", pn[pass], ds, kSConvBand, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConvNT);
     if (l.kind == KIND_SFILTER16)
         return snprintf(buf, n, "sfilter16 %s %s rows%d splitk%d grid%dx%d threads%ld", pn[pass], ds, kSFilter16TP, l.splits,

@@ -5,12 +5,14 @@
 // floats in the NHWC image, so a window row is read as SLOTS = round4(S*C + LPAD)
 // consecutive floats starting LPAD floats left of the window (16-byte aligned for
 // every window because stride_w*C is a multiple of 4); the extra slots meet zero
-// weights.  A work-group keeps the (TP-1)*stride_h + R input rows that TP = 4
-// output rows touch in LDS, zero padding included, and walks the reduction index
-// t = r*SLOTS + jj in steps of 40 slots, streaming the matching slice of the
-// re-laid-out filters w2[k][t] through a double-buffered LDS tile.  Eight
-// wavefronts each own 32 output pixels x 64 filters.  Work-groups loop over
-// (image, 4-row band) units with the next band prefetched into registers.
+// weights.  A work-group takes a band of 256 consecutive output pixels of one image
+// (row-major, so a band starts and ends anywhere in a row: whole rows of 55 pixels
+// would leave 36 of 256 MFMA rows empty), keeps the input rows those pixels touch in
+// LDS, zero padding included, and walks the reduction index t = r*SLOTS + jj in
+// steps of 40 slots, streaming the matching slice of the re-laid-out filters
+// w2[k][t] through a double-buffered LDS tile.  Eight wavefronts each own 32 output
+// pixels x 64 filters.  Work-groups loop over (image, band) units with the next
+// band prefetched into registers.
 #pragma once
 #include "igemm.hpp"
 
@@ -19,7 +21,7 @@ namespace owt {
 struct SConvGeom {
     int SEG, LPAD, SLOTS, PITCH, ROWS, ZROWS, KSLOTS, KSTEPS, units_per_image, units, units_per_wg, MPIX;
 };
-constexpr int kSConvNT = 512, kSConvTP = 4, kSConvBK = 40, kSConvPNP = 8;
+constexpr int kSConvNT = 512, kSConvBand = 256, kSConvBK = 40, kSConvPNP = 11;
 
 // w2[k][t] = w[k][r][jj - LPAD] for t = r*SLOTS + jj inside the filter, else 0 (fp32, K x KSLOTS)
 template <class T>
@@ -37,7 +39,7 @@ __global__ void __launch_bounds__(256) sconv_pack_filters_kernel(const T *__rest
 template <class T>
 __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams p, const SConvGeom sg, const float *w2)
 {
-    constexpr int NT = kSConvNT, TP = kSConvTP, BK = kSConvBK, WP = BK + 4, KB = 64, PNP = kSConvPNP;
+    constexpr int NT = kSConvNT, BAND = kSConvBand, BK = kSConvBK, WP = BK + 4, KB = 64, PNP = kSConvPNP;
     constexpr int BQ = BK / 4;                                  // quads per step
     extern __shared__ __attribute__((aligned(16))) float slds[];
     float *Bs = slds;                                           // 2 x KB x WP
@@ -48,11 +50,7 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     const int li = lane & 31, lh = lane >> 5;
     const int k0 = blockIdx.x * KB;
 
-    // the pixel this lane feeds to the MFMA: slot m of the band's TP*Q pixels
-    const int m = wave * 32 + li;
-    const int pl = m / g.Q, q = m - pl * g.Q;
-    const bool mvalid = m < sg.MPIX;
-    const int abase = mvalid ? pl * g.sh * sg.PITCH + q * g.sw * g.C : sg.ROWS * sg.PITCH;
+    const int PQ = g.P * g.Q;
     const int qpr = sg.SLOTS / 4;                               // quads per filter row
 
     for (int i = tid; i < sg.ZROWS * sg.PITCH; i += NT) panel[i] = 0.f;
@@ -76,8 +74,8 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
         prf[it] = i < panel_f4 ? (row | (f4 << 8)) : -1;
     }
     auto load_band = [&](int u) {
-        const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
-        const int h0 = p0 * g.sh - g.ph;
+        const int n = u / sg.units_per_image, p0 = g.dQ.div((u - n * sg.units_per_image) * BAND);
+        const int h0 = p0 * g.sh - g.ph;                        // first input row of the band's first output row
 #pragma unroll
         for (int it = 0; it < PNP; it++) {
             const int row = prf[it] & 255, f4 = prf[it] >> 8, h = h0 + row;
@@ -118,6 +116,11 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     int cur = 0;
     for (int u = u_beg; u < u_end; u++) {
         const bool more_u = u + 1 < u_end;
+        // the pixel this lane feeds to the MFMA: slot wave*32 + li of the band, relative to the band's first row
+        const int n = u / sg.units_per_image, m0 = (u - n * sg.units_per_image) * BAND;
+        const int m = m0 + wave * 32 + li, pr = g.dQ.div(m), pl = pr - (int)g.dQ.div(m0), q = m - pr * g.Q;
+        const bool mvalid = m < PQ;
+        const int abase = mvalid ? pl * g.sh * sg.PITCH + q * g.sw * g.C : sg.ROWS * sg.PITCH;
         float16v acc[2];
 #pragma unroll
         for (int i = 0; i < 2; i++)
@@ -158,13 +161,11 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
         }
         // ---- epilogue of this band: register r of lane (li, lh) is pixel slot 8*(r/4) + 4*lh + r%4 of
         // the wavefront's 32, filter li (+32 for the second accumulator)
-        const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
 #pragma unroll
         for (int r = 0; r < 16; r++) {
-            const int mm = wave * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
-            const int ppl = mm / g.Q, qq = mm - ppl * g.Q, pp = p0 + ppl;
-            if (mm >= sg.MPIX || pp >= g.P) continue;
-            const size_t row = ((size_t)n * g.P + pp) * g.Q + qq;
+            const int mm = m0 + wave * 32 + 8 * (r / 4) + 4 * lh + (r % 4);
+            if (mm >= PQ) continue;
+            const size_t row = (size_t)n * PQ + mm;
 #pragma unroll
             for (int i = 0; i < 2; i++) {
                 const int k = k0 + 32 * i + li;
