@@ -178,7 +178,7 @@ static bool sfilter_geom(const Geom &g, SFilterGeom &sg)
     const int a = g.pw * g.C + sg.LPAD + g.W * g.C, b = (g.Q - 1) * g.sw * g.C + sg.SLOTS;
     sg.PITCH = ((a > b ? a : b) + 3) & ~3;
     sg.ROWS = g.sh + g.R;                         // two output rows
-    sg.NB = (g.R * sg.SLOTS + 31) / 32;
+    sg.NB = (g.R * sg.SEG + 31) / 32;             // blocks of 32 densely packed (r, s, c) slots
     sg.DZP = (2 * g.Q + 1) & ~1;
     sg.units_per_image = (g.P + 1) / 2;
     sg.units = g.N * sg.units_per_image;

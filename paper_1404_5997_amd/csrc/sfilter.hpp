@@ -7,12 +7,13 @@
 // of floats in the NHWC image.  A work-group therefore keeps the input rows that
 // TP = 2 output rows touch ((TP-1)*sh + R rows) in LDS, each row laid out with
 // its zero padding, plus the dz values of those 2*Q pixels, and computes
-//   acc[k][t] += dz[pix][k] * row[base(pix) + off(t)],   t = r*SLOTS + jj
-// where a filter row is SLOTS = round4(S*C + LPAD) consecutive floats starting
-// LPAD floats left of the window so that every window start is 16-byte aligned.
-// The 2 x NB accumulator blocks (64 filters x 32-slot blocks) are dealt to the
-// eight wavefronts of the work-group; slots that are padding are simply not stored.  The pixel
-// range is split over the grid and summed by splitk_reduce_kernel.
+//   acc[k][t] += dz[pix][k] * row[base(pix) + off(t)],   t = r*(S*C) + j
+// The window values are gathered with 4-byte LDS reads, one per lane, so the slots t are packed
+// densely (no alignment slots between filter rows: 363 slots = 12 blocks of 32 for 11x11x3, where a
+// layout with 16-byte aligned rows needs 13 and leaves a quarter of the MFMAs on empty blocks).
+// The 2 x NB accumulator blocks (64 filters x 32-slot blocks) are dealt to the eight wavefronts of the
+// work-group, ACCS (3 or 4) each.  The pixel range is split over the grid and summed by
+// splitk_reduce_kernel.
 #pragma once
 #include "igemm.hpp"
 
@@ -22,7 +23,7 @@ struct SFilterGeom {
     int SEG, LPAD, SLOTS, PITCH, ROWS, NB, units_per_image, units, units_per_wg, DZP;
 };
 // float4 staged per thread and unit: input rows (kSFilterPNP) and dz rows (kSFilterDNP)
-constexpr int kSFilterNT = 512, kSFilterACCS = 4, kSFilterPNP = 5, kSFilterDNP = 4;
+constexpr int kSFilterNT = 512, kSFilterACCS = 4, kSFilterPNP = 5, kSFilterDNP = 4;      // ACCS: the larger of the two instantiations
 
 template <class T, int NT, int ACCS, int PNP, int DNP>
 __global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, const SFilterGeom sg)
@@ -46,8 +47,8 @@ __global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, cons
 #pragma unroll
     for (int a = 0; a < ACCS; a++) {
         const int t = 32 * (nb0 + (NT / 128) * a) + li;
-        const int r = t / sg.SLOTS, jj = t - r * sg.SLOTS;
-        toff[a] = (nb0 + (NT / 128) * a < sg.NB && r < g.R) ? r * sg.PITCH + jj : 0;
+        const int r = t / sg.SEG, j = t - r * sg.SEG;
+        toff[a] = (nb0 + (NT / 128) * a < sg.NB && r < g.R) ? r * sg.PITCH + sg.LPAD + j : 0;
     }
     float16v acc[ACCS];
 #pragma unroll
@@ -170,20 +171,19 @@ __global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, cons
         __syncthreads();
     }
 
-    // ---- epilogue: slot t = r*SLOTS + jj holds dw[k][r][jj - LPAD] when 0 <= jj - LPAD < S*C
+    // ---- epilogue: slot t = r*(S*C) + j holds dw[k][r][j], which is element t of filter k
     const bool part = p.splits > 1;
     float *pout = part ? p.partial + (size_t)split * p.M * p.Ncols : nullptr;
     float *out = (float *)p.out;
 #pragma unroll
     for (int a = 0; a < ACCS; a++) {
         const int nb = nb0 + (NT / 128) * a, t = 32 * nb + li;
-        const int r = t / sg.SLOTS, j = t - r * sg.SLOTS - sg.LPAD;
-        if (nb >= sg.NB || r >= g.R || j < 0 || j >= sg.SEG) continue;
+        if (nb >= sg.NB || t >= g.R * sg.SEG) continue;
 #pragma unroll
         for (int rr = 0; rr < 16; rr++) {
             const int k = k0 + mb * 32 + 8 * (rr / 4) + 4 * lh + (rr % 4);
             if (k >= g.K) continue;
-            const size_t o = ((size_t)k * g.R + r) * sg.SEG + j;
+            const size_t o = (size_t)k * g.R * sg.SEG + t;
             if (part) pout[o] = acc[a][rr];
             else out[o] = p.alpha * acc[a][rr] + (p.beta != 0.f ? p.beta * out[o] : 0.f);
         }

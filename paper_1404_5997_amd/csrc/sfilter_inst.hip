@@ -17,18 +17,26 @@ typedef float TT;
 #define OWT_FN owt_launch_sfilter_f32
 #endif
 
-hipError_t OWT_FN(const GemmParams &p, const SFilterGeom &sg, int ktiles, hipStream_t s)
+template <int ACCS>
+static hipError_t go(const GemmParams &p, const SFilterGeom &sg, int ktiles, size_t lds, hipStream_t s)
 {
-    const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
     static bool attr_set = false;     // benign race: the attribute is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)sfilter_kernel<TT, kSFilterNT, kSFilterACCS, kSFilterPNP, kSFilterDNP>,
+        hipError_t e = hipFuncSetAttribute((const void *)sfilter_kernel<TT, kSFilterNT, ACCS, kSFilterPNP, kSFilterDNP>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((sfilter_kernel<TT, kSFilterNT, kSFilterACCS, kSFilterPNP, kSFilterDNP>), dim3(ktiles, p.splits), dim3(kSFilterNT), lds, s, p, sg);
-    hipError_t e = hipGetLastError();
+    hipLaunchKernelGGL((sfilter_kernel<TT, kSFilterNT, ACCS, kSFilterPNP, kSFilterDNP>), dim3(ktiles, p.splits), dim3(kSFilterNT), lds, s, p, sg);
+    return hipGetLastError();
+}
+
+hipError_t OWT_FN(const GemmParams &p, const SFilterGeom &sg, int ktiles, hipStream_t s)
+{
+    const size_t lds = ((size_t)sg.ROWS * sg.PITCH + (size_t)sg.DZP * 68) * 4 + (size_t)sg.DZP * 4;
+    if (sg.NB > 4 * kSFilterACCS) return hipErrorInvalidValue;
+    // three accumulator blocks per wavefront when they cover the filter (11x11x3: 12 blocks), else four
+    hipError_t e = sg.NB <= 12 ? go<3>(p, sg, ktiles, lds, s) : go<kSFilterACCS>(p, sg, ktiles, lds, s);
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
     return e;
 }
