@@ -55,14 +55,14 @@ __global__ void __launch_bounds__(64 * WK * WC, (OCC * WK * WC >= 4 ? OCC * WK *
     constexpr int PAD = OCC >= 2 ? 16 : 32, PA = KT + PAD, PB = CT + PAD;
     static_assert(OCC >= 2 || ((2 * PA) % 256 == 64 || (2 * PA) % 256 == 192), "dz rows must fall on disjoint banks");
     static_assert(OCC >= 2 || ((2 * PB) % 256 == 64 || (2 * PB) % 256 == 192), "panel rows must fall on disjoint banks");
-    constexpr int KO = KT / 8, ARPP = NT / KO, ANP = BP / ARPP;                  // dz loader (16-byte pieces)
+    constexpr int KO = KT / 8, ARPP = NT / KO, ANP = (BP + ARPP - 1) / ARPP;     // dz loader (16-byte pieces); the last pass may be partial
     // x panel loader: a thread fetches LPT 16-byte pieces of one panel row (pieces bq, bq + TPR, ...), so the
     // row's position in the padded image is worked out once per LPT loads (one piece per thread where the
     // rounding up to whole passes would cost the six-wavefront variant staging registers it does not have)
     constexpr int CO = CT / 8, LPT = CO >= 16 ? 4 : (NT % 256 == 0 ? 2 : 1), TPR = CO / LPT, BRPP = NT / TPR,
                   BNP = (PRF + BRPP - 1) / BRPP;
     constexpr int NG = BP / 16;                                  // 16-pixel MFMA groups per chunk
-    static_assert(CO % LPT == 0 && NT % TPR == 0 && BP % ARPP == 0 && NT % KO == 0, "tiles must split evenly over the threads");
+    static_assert(CO % LPT == 0 && NT % TPR == 0 && NT % KO == 0, "tiles must split evenly over the threads");
 
     __shared__ __attribute__((aligned(16))) uint16_t dzs[2][BP * PA];
     __shared__ __attribute__((aligned(16))) uint16_t panel[2][PRF * PB];
@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(64 * WK * WC, (OCC * WK * WC >= 4 ? OCC * WK *
         for (int i = 0; i < ANP; i++) {
             const int pix = pix0 + arow0 + i * ARPP, k = k0 + ako * 8;
             uint4 v = zero4;
-            if (pix < npix && k < g.K) {
+            if ((BP % ARPP == 0 || arow0 + i * ARPP < BP) && pix < npix && k < g.K) {
                 const int off = pix * g.K + k;
                 v = *(const uint4 *)(dzsrc + off);
                 if (mask) {
@@ -146,7 +146,7 @@ __global__ void __launch_bounds__(64 * WK * WC, (OCC * WK * WC >= 4 ? OCC * WK *
     auto store_chunk = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < ANP; i++)
-            *(uint4 *)(dzs[buf] + (arow0 + i * ARPP) * PA + ako * 8) = areg[i];
+            if (BP % ARPP == 0 || arow0 + i * ARPP < BP) *(uint4 *)(dzs[buf] + (arow0 + i * ARPP) * PA + ako * 8) = areg[i];
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
             const int row = brow0 + i * BRPP;

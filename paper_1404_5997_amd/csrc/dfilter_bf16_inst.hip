@@ -25,6 +25,7 @@ hipError_t owt_launch_dfilter16(int variant, const GemmParams &p, hipStream_t s)
     case 4: return go<4>(p, s);
     case 5: return go<5>(p, s);
     case 6: return go<6>(p, s);
+    case 7: return go<7>(p, s);
     default: return hipErrorInvalidValue;
     }
 }

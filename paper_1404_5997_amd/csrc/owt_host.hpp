@@ -61,13 +61,14 @@ hipError_t owt_launch_dfilter_bf16(int variant, const GemmParams &, hipStream_t)
 // 32*WC channels, 64-pixel chunks, tmax taps per work-group, prf panel rows, occ work-groups per CU.
 // Variants 4 and 5 cover the tiles of 0 and 2 with twice the wavefronts of half the filter block each
 // (two wavefronts per SIMD instead of one: more LDS reads per MFMA, but one wavefront's waits are
-// filled by the other), variant 6 the tile of 3 with twelve wavefronts of one filter block.  Sixteen
+// filled by the other), variant 6 the tile of 3 with twelve wavefronts of one filter block, variant 7 a
+// 128 x 192 tile (twelve wavefronts of two filter blocks; 192 channels in one tile, 156 KB of LDS).  Sixteen
 // wavefronts of one block on the 128 x 128 tile were slower again: the LDS reads then bound the kernel.
 struct DFilter16Variant { int WK, WC, KB, tmax, prf, occ; };
-constexpr int kNumDFilter16Variants = 7;
+constexpr int kNumDFilter16Variants = 8;
 constexpr DFilter16Variant kDFilter16Variants[kNumDFilter16Variants] = {
     {1, 4, 4, 3, 128, 1}, {2, 2, 2, 5, 224, 1}, {1, 2, 4, 3, 128, 2}, {3, 2, 2, 5, 224, 1}, {2, 4, 2, 3, 128, 1}, {2, 2, 2, 3, 128, 2},
-    {6, 2, 1, 5, 224, 1}};
+    {6, 2, 1, 5, 224, 1}, {2, 6, 2, 3, 128, 1}};
 constexpr int kDFilter16BP = 64;
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 

@@ -193,7 +193,7 @@ def test_bf16_mfma_direct_kernel(tile, split):
             os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (6, 1), (0, 3), (1, 4), (2, 7), (3, 5), (4, 2), (5, 6), (6, 3)])
+@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (6, 1), (7, 1), (0, 3), (1, 4), (2, 7), (3, 5), (4, 2), (5, 6), (6, 3), (7, 4)])
 def test_bf16_mfma_filter_gradient_kernel(variant, split):
     # bf16 storage, stride 1, "same" padding, channels and filters multiples of 8: the filter gradient runs on
     # the bf16 MFMA, one filter row per work-group (3-tap variants 0, 2, 4, 5; 5-tap variants 1, 3, 6)
