@@ -401,6 +401,14 @@ def test_fc_backward_pair(mode):
         os.environ.pop(mode, None)
 
 
+def test_fc_dense_kernel_degenerate_sizes():
+    # one image, one column, a single reduction step, a reduction shorter than one step: every operand tile is
+    # mostly clamped re-reads and the padded dz copy is mostly padding
+    for (N, I, O), relu in [((1, 32, 1), False), ((1, 64, 125), True), ((2, 4, 3), True), ((33, 36, 5), False), ((128, 32, 512), True)]:
+        fc_parity(N, I, O, 1, relu, seed=970)
+        fc_parity(N, I, O, 1, relu, seed=971, alpha=0.5, beta=1.0)
+
+
 def test_fc_shard_bwd_without_dx_or_dbias():
     m = owt()
     g = np.random.default_rng(9)
