@@ -4,12 +4,15 @@
 
 namespace owt {
 
-template <class T, int V>
+// WS = 0: window and stride at run time; WS = 3: the 3x3 stride-2 pooling of the Section 5 model, with the
+// nine loads of a window unrolled (all in flight before the first comparison).
+template <class T, int V, int WS = 0>
 __global__ void __launch_bounds__(256) maxpool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y,
                                                           unsigned char *__restrict__ am, int N, int H, int W,
-                                                          int C, int win, int st, int P, int Q, FastDiv dCv,
+                                                          int C, int win_, int st_, int P, int Q, FastDiv dCv,
                                                           FastDiv dQ, FastDiv dP)
 {
+    const int win = WS ? 3 : win_, st = WS ? 2 : st_;
     const int Cv = C / V;
     const long total = (long)N * P * Q * Cv;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
@@ -19,19 +22,36 @@ __global__ void __launch_bounds__(256) maxpool_fwd_kernel(const T *__restrict__ 
         const int c = cv * V;
         float best[V]; int bi[V];
         const int base = ((n * H + p * st) * W + q * st) * C + c;
-        for (int r = 0; r < win; r++)
-            for (int s = 0; s < win; s++) {
-                const int off = base + (r * W + s) * C;
-                float v[V];
-                if constexpr (V == 4) { const float4 t = load4(x, off); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
-                else v[0] = load1(x, off);
+        if constexpr (WS == 3 && V == 4) {
+            float4 t[9];
 #pragma unroll
-                for (int j = 0; j < V; j++)
-                    if ((r | s) == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = r * win + s; }
+            for (int rs = 0; rs < 9; rs++) t[rs] = load4(x, base + ((rs / 3) * W + rs % 3) * C);
+#pragma unroll
+            for (int rs = 0; rs < 9; rs++) {
+                const float v[4] = {t[rs].x, t[rs].y, t[rs].z, t[rs].w};
+#pragma unroll
+                for (int j = 0; j < 4; j++)
+                    if (rs == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = rs; }
             }
+        } else {
+            for (int r = 0; r < win; r++)
+                for (int s = 0; s < win; s++) {
+                    const int off = base + (r * W + s) * C;
+                    float v[V];
+                    if constexpr (V == 4) { const float4 t = load4(x, off); v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w; }
+                    else v[0] = load1(x, off);
+#pragma unroll
+                    for (int j = 0; j < V; j++)
+                        if ((r | s) == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = r * win + s; }
+                }
+        }
         const size_t o = (size_t)pix * C + c;
 #pragma unroll
-        for (int j = 0; j < V; j++) { store1(y, o + j, best[j]); am[o + j] = (unsigned char)bi[j]; }
+        for (int j = 0; j < V; j++) store1(y, o + j, best[j]);
+        if constexpr (V == 4)       // c is a multiple of 4 and so is C: one aligned 4-byte store of the four arg-max codes
+            *(uint32_t *)(am + o) = (uint32_t)bi[0] | ((uint32_t)bi[1] << 8) | ((uint32_t)bi[2] << 16) | ((uint32_t)bi[3] << 24);
+        else
+            am[o] = (unsigned char)bi[0];
     }
 }
 
@@ -90,10 +110,12 @@ __device__ __forceinline__ void unpack8(const uint4 v, float (&f)[8])
     for (int j = 0; j < 4; j++) { f[2 * j] = __uint_as_float(w[j] << 16); f[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u); }
 }
 
+template <int WS>
 __global__ void __launch_bounds__(256) maxpool_fwd_bf16x8_kernel(const uint16_t *__restrict__ x, uint16_t *__restrict__ y,
                                                                  unsigned char *__restrict__ am, int N, int H, int W, int C,
-                                                                 int win, int st, int P, int Q, FastDiv dCv, FastDiv dQ, FastDiv dP)
+                                                                 int win_, int st_, int P, int Q, FastDiv dCv, FastDiv dQ, FastDiv dP)
 {
+    const int win = WS ? 3 : win_, st = WS ? 2 : st_;
     const int Cv = C / 8;
     const long total = (long)N * P * Q * Cv;
     for (long i = (long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long)gridDim.x * 256) {
@@ -103,15 +125,29 @@ __global__ void __launch_bounds__(256) maxpool_fwd_bf16x8_kernel(const uint16_t 
         const int c = cv * 8;
         float best[8]; uint32_t bits[8]; int bi[8];
         const int base = ((n * H + p * st) * W + q * st) * C + c;
-        for (int r = 0; r < win; r++)
-            for (int s = 0; s < win; s++) {
-                const uint4 raw = *(const uint4 *)(x + base + (r * W + s) * C);
+        if constexpr (WS == 3) {
+            uint4 raw[9];
+#pragma unroll
+            for (int rs = 0; rs < 9; rs++) raw[rs] = *(const uint4 *)(x + base + ((rs / 3) * W + rs % 3) * C);
+#pragma unroll
+            for (int rs = 0; rs < 9; rs++) {
                 float v[8];
-                unpack8(raw, v);
+                unpack8(raw[rs], v);
 #pragma unroll
                 for (int j = 0; j < 8; j++)
-                    if ((r | s) == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = r * win + s; bits[j] = __float_as_uint(v[j]) >> 16; }
+                    if (rs == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = rs; bits[j] = __float_as_uint(v[j]) >> 16; }
             }
+        } else {
+            for (int r = 0; r < win; r++)
+                for (int s = 0; s < win; s++) {
+                    const uint4 raw = *(const uint4 *)(x + base + (r * W + s) * C);
+                    float v[8];
+                    unpack8(raw, v);
+#pragma unroll
+                    for (int j = 0; j < 8; j++)
+                        if ((r | s) == 0 || v[j] > best[j]) { best[j] = v[j]; bi[j] = r * win + s; bits[j] = __float_as_uint(v[j]) >> 16; }
+                }
+        }
         const size_t o = (size_t)pix * C + c;
         uint4 out;                       // the maxima are input values: their bf16 bits are copied, not re-rounded
         out.x = bits[0] | (bits[1] << 16); out.y = bits[2] | (bits[3] << 16);
@@ -300,13 +336,18 @@ owt_status owt_maxpool_fwd(int N, int H, int W, int C, int win, int stride, owt_
     FastDiv dCv, dQ, dP; dCv.set(C / V); dQ.set(Q); dP.set(P);
     const long total = (long)N * P * Q * (C / V);
     hipStream_t s = (hipStream_t)hip_stream;
-    if (V == 8)
-        hipLaunchKernelGGL(maxpool_fwd_bf16x8_kernel, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t *)x, (uint16_t *)y,
-                           argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP);
-#define OWT_POOL_F(T, VV) hipLaunchKernelGGL((maxpool_fwd_kernel<T, VV>), dim3(grid_for(total)), dim3(256), 0, s, \
+    const bool w3s2 = win == 3 && stride == 2;
+#define OWT_POOL_F(T, VV, WS) hipLaunchKernelGGL((maxpool_fwd_kernel<T, VV, WS>), dim3(grid_for(total)), dim3(256), 0, s, \
         (const T *)x, (T *)y, argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP)
-    else if (dtype == OWT_F32) { if (V == 4) OWT_POOL_F(float, 4); else OWT_POOL_F(float, 1); }
-    else { if (V == 4) OWT_POOL_F(bf16_t, 4); else OWT_POOL_F(bf16_t, 1); }
+    if (V == 8) {
+        if (w3s2) hipLaunchKernelGGL(maxpool_fwd_bf16x8_kernel<3>, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t *)x, (uint16_t *)y,
+                                     argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP);
+        else hipLaunchKernelGGL(maxpool_fwd_bf16x8_kernel<0>, dim3(grid_for(total)), dim3(256), 0, s, (const uint16_t *)x, (uint16_t *)y,
+                                argmax, N, H, W, C, win, stride, P, Q, dCv, dQ, dP);
+    } else if (dtype == OWT_F32) {
+        if (V == 4) { if (w3s2) OWT_POOL_F(float, 4, 3); else OWT_POOL_F(float, 4, 0); }
+        else OWT_POOL_F(float, 1, 0);
+    } else { if (V == 4) OWT_POOL_F(bf16_t, 4, 0); else OWT_POOL_F(bf16_t, 1, 0); }
 #undef OWT_POOL_F
     const hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(OWT_ELAUNCH, "HIP launch failed: %s", hipGetErrorString(e));
