@@ -265,23 +265,39 @@ __global__ void __launch_bounds__(256) maxpool_bwd_w3s2_kernel(const T *__restri
             for (int wc = 0; wc < 2; wc++)
 #pragma unroll
                 for (int j = 0; j < V; j++) acc[hr][wc][j] = 0.f;
+        // the (up to) four windows that reach into this 2x2 block; a window outside the pooled map is read at a
+        // clamped position and its gradient zeroed, so that all loads are issued before the first use
+        int code[2][2][V];
+        float g[2][2][V];
+        size_t off[2][2];
+        bool ok[2][2];
 #pragma unroll
         for (int dp = 0; dp < 2; dp++)
 #pragma unroll
             for (int dq = 0; dq < 2; dq++) {
                 const int p = a - 1 + dp, q = b - 1 + dq;
-                if ((unsigned)p >= (unsigned)P || (unsigned)q >= (unsigned)Q) continue;
-                const size_t off = ((size_t)(n * P + p) * Q + q) * C + c;
-                int code[V];
-                float g[V];
-                PoolVec<T, V>::codes(am, off, code);
-                PoolVec<T, V>::load(dy, off, g);
-                if (yp) {   // fused ReLU backward: a window whose maximum is <= 0 passes nothing
-                    float y[V];
-                    PoolVec<T, V>::load(yp, off, y);
+                ok[dp][dq] = (unsigned)p < (unsigned)P && (unsigned)q < (unsigned)Q;
+                off[dp][dq] = ((size_t)(n * P + min(max(p, 0), P - 1)) * Q + min(max(q, 0), Q - 1)) * C + c;
+                PoolVec<T, V>::codes(am, off[dp][dq], code[dp][dq]);
+                PoolVec<T, V>::load(dy, off[dp][dq], g[dp][dq]);
+            }
+        if (yp) {   // fused ReLU backward: a window whose maximum is <= 0 passes nothing
+            float y[2][2][V];
 #pragma unroll
-                    for (int j = 0; j < V; j++) g[j] = y[j] > 0.f ? g[j] : 0.f;
-                }
+            for (int dp = 0; dp < 2; dp++)
+#pragma unroll
+                for (int dq = 0; dq < 2; dq++) PoolVec<T, V>::load(yp, off[dp][dq], y[dp][dq]);
+#pragma unroll
+            for (int dp = 0; dp < 2; dp++)
+#pragma unroll
+                for (int dq = 0; dq < 2; dq++)
+#pragma unroll
+                    for (int j = 0; j < V; j++) g[dp][dq][j] = y[dp][dq][j] > 0.f ? g[dp][dq][j] : 0.f;
+        }
+#pragma unroll
+        for (int dp = 0; dp < 2; dp++)
+#pragma unroll
+            for (int dq = 0; dq < 2; dq++) {
                 // window row r lands on block row (dp == 1 ? r : r - 2), likewise for columns
 #pragma unroll
                 for (int hr = 0; hr < 2; hr++)
@@ -291,7 +307,7 @@ __global__ void __launch_bounds__(256) maxpool_bwd_w3s2_kernel(const T *__restri
                         if (r > 2 || sc > 2) continue;           // compile-time: that element is outside this window
 #pragma unroll
                         for (int j = 0; j < V; j++)
-                            if (code[j] == 3 * r + sc) acc[hr][wc][j] += g[j];
+                            if (ok[dp][dq] && code[dp][dq][j] == 3 * r + sc) acc[hr][wc][j] += g[dp][dq][j];
                     }
             }
 #pragma unroll
