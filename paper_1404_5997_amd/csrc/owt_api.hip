@@ -126,7 +126,10 @@ static bool sconv16_geom(const Geom &g, SConv16Geom &sg)
     sg.MPIX = kSConv16TP * g.Q;
     sg.units_per_image = (g.P + kSConv16TP - 1) / kSConv16TP;
     sg.units = g.N * sg.units_per_image;
-    const size_t lds = ((size_t)64 * sg.WP + (size_t)2 * sg.ZROWS * sg.PITCH) * 2;     // filter bank + two bands
+    sg.BIAS = 64 * sg.WP + 2 * sg.ZROWS * sg.PITCH;
+    const size_t lds = ((size_t)sg.BIAS + 128) * 2;                  // filter bank + two bands + 64 fp32 biases
+    // the output staging blocks follow when the 160 KB of a CU still hold them
+    sg.STAGE = lds + (size_t)kSConv16StageValues * 2 <= 160 * 1024 ? (int)(lds / 2) : 0;
     return sg.OCT >= 2 && sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 &&
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)(kSConv16NT / 2) * kSConv16PNP;
 }

@@ -24,8 +24,12 @@ namespace owt {
 
 struct SConv16Geom {
     int SEG, LPAD, SLOTS, OCT, NG, KSLOTS, WP, PITCH, ROWS, ZROWS, MPIX, units_per_image, units, units_per_wg;
+    int BIAS;       // LDS offset (values) of the 64 fp32 biases of the work-group's filters
+    int STAGE;      // LDS offset (values) of the output staging blocks, 0 when they do not fit
 };
 constexpr int kSConv16NT = 512, kSConv16TP = 4, kSConv16PNP = 16;
+constexpr int kSConv16EP = 64 + 4;                               // staging row of one pixel: 136 bytes, conflict-free 8-byte writes
+constexpr int kSConv16StageValues = (kSConv16NT / 64) * 32 * kSConv16EP;    // one 32-pixel block per wavefront
 
 typedef __bf16 sc16_bf16x8 __attribute__((ext_vector_type(8)));
 
@@ -68,6 +72,9 @@ __global__ void __launch_bounds__(kSConv16NT, 1) sconv16_fwd_kernel(const GemmPa
             *(uint4 *)(Bs + line * sg.WP + o * 8) = v;
         }
     }
+    // the biases of the 64 filters wait in LDS for the epilogues (32 registers per lane otherwise)
+    float *biasl = (float *)(s16 + sg.BIAS);
+    if (threadIdx.x < KB) biasl[threadIdx.x] = ((p.flags & 1u) && k0 + (int)threadIdx.x < g.K) ? p.bias[k0 + threadIdx.x] : 0.f;
     __syncthreads();
 
     // the two pixels this lane feeds to the MFMA (B operand): slots m of the band's TP*Q pixels.
@@ -118,15 +125,10 @@ __global__ void __launch_bounds__(kSConv16NT, 1) sconv16_fwd_kernel(const GemmPa
     __syncthreads();
 
     uint16_t *out = (uint16_t *)p.out;
-    const bool has_bias = (p.flags & 1u) != 0, relu = (p.flags & 2u) != 0;
-    float4 bias4[2][4];                                          // this lane's 8 quads of filters
-#pragma unroll
-    for (int bk = 0; bk < 2; bk++)
-#pragma unroll
-        for (int rq = 0; rq < 4; rq++) {
-            const int k = k0 + 32 * bk + 8 * rq + 4 * lh;
-            bias4[bk][rq] = (has_bias && k < g.K) ? *(const float4 *)(p.bias + k) : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+    constexpr int EP = kSConv16EP;
+    const bool staged = sg.STAGE > 0 && (g.K & 7) == 0;          // 16-byte output pieces need K % 8 == 0
+    uint16_t *stage = s16 + sg.STAGE + (threadIdx.x >> 6) * 32 * EP;
+    const bool relu = (p.flags & 2u) != 0;
     // both halves run the same number of rounds (the barriers are work-group wide); a half without a
     // band in the last round computes on its stale rows and stores nothing
     for (int u0 = u_beg; u0 < u_end; u0 += 2) {
@@ -186,29 +188,64 @@ __global__ void __launch_bounds__(kSConv16NT, 1) sconv16_fwd_kernel(const GemmPa
         const int n = u / sg.units_per_image, p0 = (u - n * sg.units_per_image) * TP;
         const int mlim = have ? min(sg.MPIX, (g.P - p0) * g.Q) : 0;
         const size_t pix0 = ((size_t)n * g.P + p0) * g.Q;
+        if (staged) {
+            // Results leave through LDS, 32 pixels x 64 filters per wavefront and pass: a lane writes its
+            // 8-byte pieces, then the wavefront reads the block back pixel by pixel and stores 16 bytes per
+            // lane, eight lanes to the 128-byte line of a pixel (stored straight from the accumulators a
+            // store instruction touches 32 lines with 16 bytes each).  Each wavefront stages in a block of
+            // its own, so program order is all the synchronisation this needs.
 #pragma unroll
-        for (int bm = 0; bm < 2; bm++) {
-            const int m = wave * 64 + bm * 32 + li;
-            if (m >= mlim) continue;
+            for (int bm = 0; bm < 2; bm++) {
 #pragma unroll
-            for (int bk = 0; bk < 2; bk++)
+                for (int bk = 0; bk < 2; bk++)
 #pragma unroll
-                for (int rq = 0; rq < 4; rq++) {
-                    const int k = k0 + 32 * bk + 8 * rq + 4 * lh;
-                    if (k >= g.K) continue;                      // K is a multiple of 4: whole quads are in or out
-                    float v[4];
+                    for (int rq = 0; rq < 4; rq++) {
+                        float v[4];
 #pragma unroll
-                    for (int j = 0; j < 4; j++) v[j] = acc[bk][bm][4 * rq + j];
-                    v[0] += bias4[bk][rq].x; v[1] += bias4[bk][rq].y; v[2] += bias4[bk][rq].z; v[3] += bias4[bk][rq].w;
-                    if (relu) {
+                        for (int j = 0; j < 4; j++) v[j] = acc[bk][bm][4 * rq + j];
+                        const float4 b4 = *(const float4 *)(biasl + 32 * bk + 8 * rq + 4 * lh);
+                        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+                        if (relu) {
 #pragma unroll
-                        for (int j = 0; j < 4; j++) v[j] = v[j] > 0.f ? v[j] : 0.f;
+                            for (int j = 0; j < 4; j++) v[j] = v[j] > 0.f ? v[j] : 0.f;
+                        }
+                        *(uint2 *)(stage + li * EP + 32 * bk + 8 * rq + 4 * lh) =
+                            make_uint2(f32x2_to_bf16x2(v[0], v[1]), f32x2_to_bf16x2(v[2], v[3]));
                     }
-                    uint2 o;
-                    o.x = f32x2_to_bf16x2(v[0], v[1]);
-                    o.y = f32x2_to_bf16x2(v[2], v[3]);
-                    *(uint2 *)(out + (pix0 + m) * g.K + k) = o;
+#pragma unroll
+                for (int q = 0; q < 4; q++) {
+                    const int row = q * 8 + (lane >> 3), kl = (lane & 7) * 8;
+                    const int m = wave * 64 + bm * 32 + row;
+                    const uint4 v = *(const uint4 *)(stage + row * EP + kl);
+                    if (m < mlim && k0 + kl < g.K) *(uint4 *)(out + (pix0 + m) * g.K + k0 + kl) = v;
                 }
+            }
+        } else {
+#pragma unroll
+            for (int bm = 0; bm < 2; bm++) {
+                const int m = wave * 64 + bm * 32 + li;
+                if (m >= mlim) continue;
+#pragma unroll
+                for (int bk = 0; bk < 2; bk++)
+#pragma unroll
+                    for (int rq = 0; rq < 4; rq++) {
+                        const int k = k0 + 32 * bk + 8 * rq + 4 * lh;
+                        if (k >= g.K) continue;                      // K is a multiple of 4: whole quads are in or out
+                        float v[4];
+#pragma unroll
+                        for (int j = 0; j < 4; j++) v[j] = acc[bk][bm][4 * rq + j];
+                        const float4 b4 = *(const float4 *)(biasl + 32 * bk + 8 * rq + 4 * lh);
+                        v[0] += b4.x; v[1] += b4.y; v[2] += b4.z; v[3] += b4.w;
+                        if (relu) {
+#pragma unroll
+                            for (int j = 0; j < 4; j++) v[j] = v[j] > 0.f ? v[j] : 0.f;
+                        }
+                        uint2 o;
+                        o.x = f32x2_to_bf16x2(v[0], v[1]);
+                        o.y = f32x2_to_bf16x2(v[2], v[3]);
+                        *(uint2 *)(out + (pix0 + m) * g.K + k) = o;
+                    }
+            }
         }
 
         if (u0 + 2 < u_end) {                                    // uniform over the work-group

@@ -6,10 +6,10 @@ namespace owt {
 
 hipError_t owt_launch_sconv16(const GemmParams &p, const SConv16Geom &sg, int ktiles, int nwg, void *w2, hipStream_t s)
 {
-    const size_t lds = ((size_t)64 * sg.WP + (size_t)2 * sg.ZROWS * sg.PITCH) * 2;
+    const size_t lds = ((size_t)sg.BIAS + 128 + (sg.STAGE > 0 ? kSConv16StageValues : 0)) * 2;
     static bool attr_set = false;     // benign race: the attribute is idempotent
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)sconv16_fwd_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 152 * 1024);
+        hipError_t e = hipFuncSetAttribute((const void *)sconv16_fwd_kernel<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
