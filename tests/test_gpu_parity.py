@@ -216,7 +216,11 @@ def test_bf16_mfma_filter_gradient_kernel(variant, split):
 
 @pytest.mark.parametrize("shape,split", [
     ((5, 4, 23, 20, 8, 7, 7, 4, 2), 3), ((2, 3, 24, 24, 72, 7, 7, 4, 3), 0), ((3, 3, 36, 28, 64, 11, 11, 4, 2), 5),
-    ((2, 8, 17, 12, 20, 5, 3, (2, 2), (2, 1)), 2), ((2, 3, 224, 224, 64, 11, 11, 4, 2), 0)])
+    ((2, 8, 17, 12, 20, 5, 3, (2, 2), (2, 1)), 2), ((2, 3, 224, 224, 64, 11, 11, 4, 2), 0),
+    # six 4-row bands over 2 and over 6 work-groups: three bands or one band each, so the second half of a
+    # work-group's wavefronts (the bf16 forward kernel runs two bands half a round apart) ends a round early
+    # or has no band at all
+    ((3, 3, 36, 28, 64, 11, 11, 4, 2), 2), ((3, 3, 36, 28, 64, 11, 11, 4, 2), 6)])
 def test_strided_small_channel_kernels(shape, split):
     # first-layer style geometry: the row-panel forward and filter-gradient kernels, forced, with and
     # without a forced work-group count
