@@ -236,6 +236,24 @@ owt_status owt_logistic_xent(int N, int O_local, int col_offset, owt_dtype dtype
  * Points at thread-local static storage; valid until the thread's next call. */
 const char *owt_last_error(void);
 
+/* TEST HOOK -- not part of the computation's interface.  The library's test suite has to run every
+ * kernel instantiation, also those the planner would not pick for a small test shape.  This call
+ * overrides the planner for ALL later calls of the process until it is called again with
+ * (-1, 0, 0): `tile` >= 0 restricts the candidates to that tile / variant number of whichever kernel
+ * family serves the pass (16..19 are the dense shard kernel's four tiles), `splitk` > 0 forces the
+ * split count of the reduction (clamped to the number of reduction steps), `flags` is a set of
+ * OWT_FORCE_* bits.  While an override is active, tuned and cached plans are ignored.  The three
+ * values are stored atomically, but a launch that runs concurrently with this call may see the old
+ * or the new setting: production code has no reason to call it. */
+enum {
+    OWT_FORCE_NO_DIRECT = 1u,       /* gather kernel only                                              */
+    OWT_FORCE_ONLY_DIRECT = 2u,     /* never the gather kernel when another one qualifies              */
+    OWT_FORCE_NO_BF16_MFMA = 4u,    /* bf16 storage on the fp32-MFMA kernels (widening loads)          */
+    OWT_FORCE_FC_ONE_LAUNCH = 8u,   /* owt_fc_shard_bwd: both products in one launch                   */
+    OWT_FORCE_FC_TWO_LAUNCHES = 16u /* owt_fc_shard_bwd: one launch per product                        */
+};
+void owt_test_force_variant(int tile, int splitk, unsigned flags);
+
 /* Library ABI version (bumped on any signature change). */
 int owt_abi_version(void);
 

@@ -18,13 +18,15 @@ OWT_OK, OWT_EINVAL, OWT_EUNSUPPORTED, OWT_EWORKSPACE, OWT_ELAUNCH = 0, 1, 2, 3, 
 OWT_F32, OWT_BF16 = 0, 1
 OWT_BIAS, OWT_RELU = 1, 2
 OWT_PASS_FWD, OWT_PASS_BWD_DATA, OWT_PASS_BWD_FILTER = 0, 1, 2
+OWT_FORCE_NO_DIRECT, OWT_FORCE_ONLY_DIRECT, OWT_FORCE_NO_BF16_MFMA = 1, 2, 4
+OWT_FORCE_FC_ONE_LAUNCH, OWT_FORCE_FC_TWO_LAUNCHES = 8, 16
 
 EXPORTS = (
     "owt_conv_workspace_bytes", "owt_fc_workspace_bytes", "owt_conv_fwd", "owt_conv_bwd_data",
     "owt_conv_bwd_filter", "owt_fc_shard_fwd", "owt_fc_shard_bwd", "owt_maxpool_fwd",
     "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe", "owt_conv_autotune",
     "owt_conv_bwd_data_relu_in", "owt_maxpool_bwd_relu", "owt_sgd_momentum_update", "owt_scale_hyperparameters",
-    "owt_logistic_xent", "owt_fc_autotune",
+    "owt_logistic_xent", "owt_fc_autotune", "owt_test_force_variant",
 )
 
 
@@ -74,6 +76,8 @@ _lib.owt_logistic_xent.argtypes = [_i, _i, _i, _i, _vp, _vp, _f, _vp, _vp, _vp]
 _lib.owt_last_error.restype = ctypes.c_char_p
 _lib.owt_abi_version.restype = _i
 _lib.owt_conv_plan_describe.argtypes = [_cd, _i, ctypes.c_char_p, _sz]
+_lib.owt_test_force_variant.argtypes = [_i, _i, ctypes.c_uint]
+_lib.owt_test_force_variant.restype = None
 
 
 def _ptr(t):
@@ -119,6 +123,10 @@ def owt_conv_plan_describe(desc, pass_):
     if n < 0:
         raise OwtError(OWT_EINVAL, owt_last_error())
     return buf.value.decode()
+
+
+def owt_test_force_variant(tile=-1, splitk=0, flags=0):
+    _lib.owt_test_force_variant(tile, splitk, flags)
 
 
 def owt_selftest_host():

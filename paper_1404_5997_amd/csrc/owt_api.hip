@@ -1,6 +1,7 @@
 // C ABI entry points of libowt: descriptor checks, launch planning, tuning, launches.
 #include <algorithm>
 #include <array>
+#include <atomic>
 #include <map>
 #include <mutex>
 #include <vector>
@@ -267,12 +268,16 @@ static double model_cost(long wgs, int waves_per_wg, int occ, double macs_per_wg
 
 static const size_t kMaxPartialBytes = (size_t)192 << 20;
 
+// What owt_test_force_variant asked for (tests only; -1 / 0 = the planner decides).
+static std::atomic<int> g_force_tile{-1}, g_force_split{-1};
+static std::atomic<unsigned> g_force_flags{0};
+static inline bool forced(unsigned bit) { return (g_force_flags.load(std::memory_order_relaxed) & bit) != 0; }
+
 static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db, std::vector<Launch> &out)
 {
-    int force_tile = -1, force_split = -1;
-    if (const char *e = getenv("OWT_TILE")) force_tile = atoi(e);
-    if (const char *e = getenv("OWT_SPLITK")) force_split = atoi(e);
-    const bool no_direct = getenv("OWT_NO_DIRECT") != nullptr;
+    const int force_tile = g_force_tile.load(std::memory_order_relaxed);
+    const int force_split = g_force_split.load(std::memory_order_relaxed);
+    const bool no_direct = forced(OWT_FORCE_NO_DIRECT);
     const bool vec = dm.va && dm.vb;
 
     auto add = [&](int kind, int tile, int pr, long steps, long s, double macs_per_step_wg, int occ, double eff) {
@@ -321,7 +326,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (force_split > 0) break;
         }
     }
-    if (g.bf16 && cred % 8 == 0 && !getenv("OWT_NO_BF16_MFMA")) {      // the bf16 MFMA: 64-channel chunks, or 32 in the 512x64 tile
+    if (g.bf16 && cred % 8 == 0 && !forced(OWT_FORCE_NO_BF16_MFMA)) {      // the bf16 MFMA: 64-channel chunks, or 32 in the 512x64 tile
         for (int t : {TILE_128x128, TILE_128x64, TILE_256x64, TILE_512x64, TILE_256x64P}) {
             if (no_direct || (force_tile >= 0 && force_tile != t)) continue;
             const long BM = kTiles[t].BM, rows = direct_panel_rows(g, pass, dm, BM);
@@ -365,7 +370,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     SConv16Geom s16g;
-    if (pass == OWT_PASS_FWD && !no_direct && !getenv("OWT_NO_BF16_MFMA") && sconv16_geom(g, s16g)) {
+    if (pass == OWT_PASS_FWD && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA) && sconv16_geom(g, s16g)) {
         const long ktiles = cdiv(g.K, 64);
         for (long target : {256L, 512L}) {
             long wgs = target / ktiles > 0 ? target / ktiles : 1;
@@ -406,7 +411,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     SFilter16Geom sf16g;
-    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !getenv("OWT_NO_BF16_MFMA") && (g.sh > 1 || g.sw > 1) &&
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA) && (g.sh > 1 || g.sw > 1) &&
         sfilter16_geom(g, sf16g)) {
         const long ktiles = cdiv(g.K, 64);
         for (long target : {256L, 512L, 1024L}) {
@@ -461,7 +466,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             }
         }
     }
-    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !getenv("OWT_NO_BF16_MFMA")) {
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA)) {
         for (int v = 0; v < kNumDFilter16Variants; v++) {
             int taps, groups;
             if (force_tile >= 0 && force_tile != v) continue;
@@ -549,17 +554,17 @@ static PlanKey plan_key(const Geom &g, int pass, owt_dtype dt)
     return PlanKey{g.N, g.C, g.H, g.W, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, pass, (int)dt, 0, 0};
 }
 
-static bool env_overrides()
+static bool variants_forced()
 {
-    return getenv("OWT_TILE") || getenv("OWT_SPLITK") || getenv("OWT_NO_DIRECT") || getenv("OWT_ONLY_DIRECT") ||
-           getenv("OWT_NO_BF16_MFMA");
+    return g_force_tile.load(std::memory_order_relaxed) >= 0 || g_force_split.load(std::memory_order_relaxed) > 0 ||
+           g_force_flags.load(std::memory_order_relaxed) != 0;
 }
 
 static std::map<PlanKey, Launch> g_modelled;   // the cost model's choice per geometry (untimed), so that a call plans once
 
 static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, bool want_db, bool use_cache)
 {
-    const bool cached = use_cache && !env_overrides();
+    const bool cached = use_cache && !variants_forced();
     if (cached) {
         std::lock_guard<std::mutex> lk(g_tuned_mutex);
         auto it = g_tuned.find(plan_key(g, pass, dt));
@@ -569,7 +574,7 @@ static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, 
     }
     std::vector<Launch> c;
     enumerate(g, pass, dm, want_db, c);
-    bool only_direct = getenv("OWT_ONLY_DIRECT") != nullptr, any_direct = false;   // test hook
+    bool only_direct = forced(OWT_FORCE_ONLY_DIRECT), any_direct = false;   // test hook
     for (const Launch &l : c) any_direct |= l.kind != KIND_GATHER;
     size_t best = c.size();
     for (size_t i = 0; i < c.size(); i++) {
@@ -801,7 +806,7 @@ static std::map<PlanKey, std::pair<bool, FcPair>> g_fc_pairs;     // planned onc
 
 static bool fc_pair_plan(const Geom &g, owt_dtype dt, FcPair &fp)
 {
-    const bool cached = !env_overrides() && !getenv("OWT_FC_TWO_LAUNCHES") && !getenv("OWT_FC_ONE_LAUNCH");
+    const bool cached = !variants_forced();
     if (cached) {
         std::lock_guard<std::mutex> lk(g_tuned_mutex);
         auto it = g_fc_pairs.find(plan_key(g, 3, dt));
@@ -814,7 +819,7 @@ static bool fc_pair_plan(const Geom &g, owt_dtype dt, FcPair &fp)
     if (fp.ld.kind == KIND_FCGEMM && fp.lf.kind == KIND_FCGEMM) {
         ok = true;
         Launch fd, ff;
-        if (!getenv("OWT_FC_TWO_LAUNCHES") && find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) &&
+        if (!forced(OWT_FORCE_FC_TWO_LAUNCHES) && find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) &&
             find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff)) {
             int fused = 1;                       // untimed: one launch
             {
@@ -822,7 +827,7 @@ static bool fc_pair_plan(const Geom &g, owt_dtype dt, FcPair &fp)
                 auto it = g_fc_fused.find(plan_key(g, 3, dt));
                 if (it != g_fc_fused.end()) fused = it->second;
             }
-            if (getenv("OWT_FC_ONE_LAUNCH")) fused = 1;
+            if (forced(OWT_FORCE_FC_ONE_LAUNCH)) fused = 1;
             if (fused) { fp.ld = fd; fp.lf = ff; fp.fused = true; }
         }
     }
@@ -849,7 +854,14 @@ using namespace owt;
 extern "C" {
 
 const char *owt_last_error(void) { return g_err; }
-int owt_abi_version(void) { return 2; }
+int owt_abi_version(void) { return 3; }
+
+void owt_test_force_variant(int tile, int splitk, unsigned flags)
+{
+    g_force_tile.store(tile < 0 ? -1 : tile);
+    g_force_split.store(splitk > 0 ? splitk : -1);
+    g_force_flags.store(flags);
+}
 
 int owt_selftest_host(void)
 {
@@ -1110,7 +1122,7 @@ owt_status owt_fc_autotune(const owt_fc_desc *d, const void *x, const void *w, c
                               hip_stream));
     // both backward products on the dense kernel: two launches (the tiles just timed) or one for both?
     Launch fd, ff;
-    if (env_overrides() || !find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) || !find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff))
+    if (variants_forced() || !find_fc_launch(g, OWT_PASS_BWD_DATA, kFcPairTile, fd) || !find_fc_launch(g, OWT_PASS_BWD_FILTER, kFcPairTile, ff))
         return OWT_OK;
     FcPair two;
     two.ld = choose(g, OWT_PASS_BWD_DATA, d->dtype, conv_dims(g, OWT_PASS_BWD_DATA), false, true);

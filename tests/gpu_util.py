@@ -13,6 +13,22 @@ def owt():
     return m
 
 
+class force:
+    """Context manager around the library's test hook owt_test_force_variant: inside the block the planner
+    is restricted to the given tile / variant number, split count and OWT_FORCE_* flags."""
+
+    def __init__(self, tile=-1, splitk=0, flags=0):
+        self.args = (tile, splitk, flags)
+
+    def __enter__(self):
+        owt().owt_test_force_variant(*self.args)
+        return self
+
+    def __exit__(self, *exc):
+        owt().owt_test_force_variant(-1, 0, 0)
+        return False
+
+
 def to_dev(a, dt="f32"):
     if a is None:
         return None

@@ -28,7 +28,7 @@ def test_every_declared_symbol_is_exported(m):
 
 def test_host_selftest(m):
     assert m.owt_selftest_host() == 0, m.owt_last_error()
-    assert m.owt_abi_version() == 2
+    assert m.owt_abi_version() == 3
 
 
 def test_bad_descriptors_are_rejected_before_any_launch(m):

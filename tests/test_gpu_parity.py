@@ -7,7 +7,6 @@ Each backward call gets the forward output y (the ReLU mask source) and the
 pooling arg-max as INPUTS, the same arrays on both sides, so every call is a
 pure function of its arguments and parity is well-posed.
 """
-import os
 import sys
 
 import numpy as np
@@ -19,7 +18,7 @@ import synthetic_inputs as si
 pytestmark = pytest.mark.gpu
 
 torch = pytest.importorskip("torch")
-from gpu_util import ConvCase, assert_close, empty, owt, prep, rel_err, to_dev, to_host, workspace  # noqa: E402
+from gpu_util import ConvCase, assert_close, empty, force, owt, prep, rel_err, to_dev, to_host, workspace  # noqa: E402
 
 
 def say(*a):
@@ -131,22 +130,18 @@ def test_flags_and_scaling_variants():
 def test_every_tile_shape_and_split_k(tile, split, direct):
     # The planner is overridden so each instantiation of the gather kernel (direct = 0) and of the
     # panel-resident stride-1 kernel (direct = 1), and the two-pass split reduction, are exercised.
-    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(tile), str(split)
-    if not direct:
-        os.environ["OWT_NO_DIRECT"] = "1"
-    try:
+    m = owt()
+    fl = 0 if direct else m.OWT_FORCE_NO_DIRECT
+    with force(tile, split, fl):
         layer_parity(4, 40, 13, 13, 136, 3, 3, 1, 1, seed=60 + tile)     # M = 676, ragged in every tile and chunk
         layer_parity(2, 32, 13, 13, 136, 3, 3, 1, 1, dt="bf16", seed=70 + tile)
-        if direct:
-            os.environ["OWT_NO_BF16_MFMA"] = "1"                             # bf16 storage on the fp32 MFMA kernel
+    if direct:
+        with force(tile, split, m.OWT_FORCE_NO_BF16_MFMA):                # bf16 storage on the fp32 MFMA kernel
             layer_parity(2, 32, 13, 13, 136, 3, 3, 1, 1, dt="bf16", seed=75 + tile)
-            os.environ.pop("OWT_NO_BF16_MFMA")
+        with force(tile, split):
             layer_parity(3, 64, 27, 27, 72, 5, 5, 1, 2, seed=80 + tile)      # 240-row panel
             layer_parity(2, 8, 9, 14, 12, 3, 5, 1, (1, 2), seed=84 + tile)   # R != S, H != W
             layer_parity(2, 8, 12, 12, 8, 3, 3, 1, 0, seed=88 + tile)        # pad 0: forward direct, bwd-data gathers
-    finally:
-        for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_DIRECT", "OWT_NO_BF16_MFMA"):
-            os.environ.pop(k, None)
 
 
 @pytest.mark.parametrize("split", [1, 7, 40])
@@ -154,17 +149,13 @@ def test_filter_gradient_with_chunks_cut_per_image(split):
     # 5x5 "same" layer on 27x27 images: 729 pixels = 22 chunks of 32 + one of 25 per image; the variant whose
     # pixel chunks never straddle two images (small panel, three work-groups per CU), forced, fp32 and bf16 storage
     m = owt()
-    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = "3", str(split)
-    try:
+    with force(3, split):
         for (N, C, K), kw in [((3, 64, 72), {}), ((1, 8, 200), dict(relu=False, alpha=0.5, beta=-0.25)), ((5, 36, 64), dict(bias=False))]:
             d = m.conv_desc(N, C, 27, 27, K, 5, 5, 1, 2, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
             assert "chunks-per-image" in m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER), m.owt_conv_plan_describe(d, 2)
             layer_parity(N, C, 27, 27, K, 5, 5, 1, 2, seed=800 + split, **kw)
-        os.environ["OWT_NO_BF16_MFMA"] = "1"
+    with force(3, split, m.OWT_FORCE_NO_BF16_MFMA):
         layer_parity(2, 64, 27, 27, 72, 5, 5, 1, 2, dt="bf16", seed=810 + split)
-    finally:
-        for k in ("OWT_TILE", "OWT_SPLITK", "OWT_NO_BF16_MFMA"):
-            os.environ.pop(k, None)
 
 
 @pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2), (7, 1), (7, 2), (7, 3), (8, 1), (8, 2)])
@@ -172,8 +163,7 @@ def test_bf16_mfma_direct_kernel(tile, split):
     # bf16 storage, stride 1, reduction channels a multiple of 8: forward and backward-data run on the
     # bf16 MFMA kernel (64-channel chunks; backward-data reads re-laid-out filters from the workspace)
     m = owt()
-    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(tile), str(split)
-    try:
+    with force(tile, split):
         shapes = [((4, 72, 13, 13, 136, 3, 3, 1), {}),                       # ragged last chunk in both passes
                   ((3, 64, 27, 27, 72, 5, 5, 2), {}),                        # 240-row panel
                   ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False)),       # one short chunk, R != S
@@ -188,9 +178,6 @@ def test_bf16_mfma_direct_kernel(tile, split):
             for ps in (m.OWT_PASS_FWD, m.OWT_PASS_BWD_DATA):
                 assert m.owt_conv_plan_describe(d, ps).startswith("dconv16"), m.owt_conv_plan_describe(d, ps)
             layer_parity(N, C, H, W, K, R, S, 1, pad, dt="bf16", seed=300 + 10 * tile + split, **kw)
-    finally:
-        for k in ("OWT_TILE", "OWT_SPLITK"):
-            os.environ.pop(k, None)
 
 
 @pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (6, 1), (7, 1), (0, 3), (1, 4), (2, 7), (3, 5), (4, 2), (5, 6), (6, 3), (7, 4)])
@@ -198,8 +185,7 @@ def test_bf16_mfma_filter_gradient_kernel(variant, split):
     # bf16 storage, stride 1, "same" padding, channels and filters multiples of 8: the filter gradient runs on
     # the bf16 MFMA, one filter row per work-group (3-tap variants 0, 2, 4, 5; 5-tap variants 1, 3, 6)
     m = owt()
-    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(variant), str(split)
-    try:
+    with force(variant, split):
         shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 9, 14, 16, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25))] \
             if variant in (1, 3, 6) else \
             [((4, 72, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
@@ -209,9 +195,6 @@ def test_bf16_mfma_filter_gradient_kernel(variant, split):
             assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("dfilter16"), \
                 m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER)
             layer_parity(N, C, H, W, K, R, S, 1, pad, dt="bf16", seed=500 + 10 * variant + split, **kw)
-    finally:
-        for k in ("OWT_TILE", "OWT_SPLITK"):
-            os.environ.pop(k, None)
 
 
 @pytest.mark.parametrize("shape,split", [
@@ -226,10 +209,7 @@ def test_strided_small_channel_kernels(shape, split):
     # without a forced work-group count
     m = owt()
     N, C, H, W, K, R, S, stride, pad = shape
-    os.environ["OWT_ONLY_DIRECT"] = "1"
-    if split:
-        os.environ["OWT_SPLITK"] = str(split)
-    try:
+    with force(-1, split, m.OWT_FORCE_ONLY_DIRECT):
         d = m.conv_desc(N, C, H, W, K, R, S, stride, pad, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
         assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("sfilter")
         assert m.owt_conv_plan_describe(d, m.OWT_PASS_FWD).startswith("sconv")
@@ -241,11 +221,8 @@ def test_strided_small_channel_kernels(shape, split):
             if K % 8 == 0:   # ... and the bf16-MFMA filter-gradient kernel
                 assert m.owt_conv_plan_describe(db, m.OWT_PASS_BWD_FILTER).startswith("sfilter16"), m.owt_conv_plan_describe(db, 2)
             layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", seed=220 + split)
-        os.environ["OWT_NO_BF16_MFMA"] = "1"                  # ... and this one the fp32-MFMA kernels on bf16 storage
+    with force(-1, split, m.OWT_FORCE_ONLY_DIRECT | m.OWT_FORCE_NO_BF16_MFMA):   # ... and the fp32-MFMA kernels on bf16 storage
         layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, seed=230 + split)
-    finally:
-        for k in ("OWT_ONLY_DIRECT", "OWT_SPLITK", "OWT_NO_BF16_MFMA"):
-            os.environ.pop(k, None)
 
 
 def test_autotune_keeps_results_and_is_remembered():
@@ -365,8 +342,7 @@ def test_fc_dense_kernel(tile, split):
     # gradient and accumulation, batch and column counts that are not multiples of 32 or 4 (the backward
     # passes then read a zero-padded copy of dz), and shapes where some or all passes do not qualify (they gather).
     m = owt()
-    os.environ["OWT_TILE"], os.environ["OWT_SPLITK"] = str(16 + tile), str(split)
-    try:
+    with force(16 + tile, split):
         for (N, I, O), ok, kw in [((160, 224, 96), (1, 1, 1), dict(relu=True)),
                                   ((128, 256, 192), (1, 1, 1), dict(relu=False, alpha=0.5, beta=-0.25)),
                                   ((100, 64, 40), (1, 1, 1), dict(relu=True)),
@@ -378,19 +354,15 @@ def test_fc_dense_kernel(tile, split):
             for ps in range(3):
                 assert ("fcgemm" in m.owt_conv_plan_describe(d, ps)) == bool(ok[ps]), (ps, m.owt_conv_plan_describe(d, ps))
             fc_parity(N, I, O, 1, seed=900 + tile, **kw)
-    finally:
-        for k in ("OWT_TILE", "OWT_SPLITK"):
-            os.environ.pop(k, None)
 
 
-@pytest.mark.parametrize("mode", ["OWT_FC_ONE_LAUNCH", "OWT_FC_TWO_LAUNCHES", "tuned"])
+@pytest.mark.parametrize("mode", ["one_launch", "two_launches", "tuned"])
 def test_fc_backward_pair(mode):
     # Both backward products of a shard on the dense kernel share one dz; they run as one launch or as two.
     # Forced either way, and chosen by owt_fc_autotune (whose timing runs must leave results unchanged).
     m = owt()
-    if mode != "tuned":
-        os.environ[mode] = "1"
-    try:
+    fl = {"one_launch": m.OWT_FORCE_FC_ONE_LAUNCH, "two_launches": m.OWT_FORCE_FC_TWO_LAUNCHES, "tuned": 0}[mode]
+    with force(-1, 0, fl):
         for (N, I, O), kw in [((128, 512, 125), dict(relu=False)), ((96, 260, 192), dict(relu=True, alpha=0.25, beta=1.0)),
                               ((33, 64, 40), dict(relu=True))]:
             if mode == "tuned":
@@ -401,8 +373,6 @@ def test_fc_backward_pair(mode):
                 m.owt_fc_autotune(d, t(N, I), t(O, I), t(O), t(N, O), t(N, O), empty((N, I), "f32"), empty((O, I), "f32"),
                                   empty((O,), "f32"), workspace(wsb))
             fc_parity(N, I, O, 1, seed=950, **kw)
-    finally:
-        os.environ.pop(mode, None)
 
 
 def test_fc_dense_kernel_degenerate_sizes():
@@ -476,7 +446,7 @@ def test_fused_relu_backward_entry_points():
         assert_close(to_host(dx), ref, dt, "maxpool_bwd_relu")
         assert (ref[y <= 0] == 0).all() and np.count_nonzero(a_ref <= 0) > 0       # the mask really bites
 
-        for (K, split) in ((40, None), (136, "3")):
+        for (K, split) in ((40, 0), (136, 3)):
             case = ConvCase(4, 24, 13, 13, K, 3, 3, 1, 1, dt, True, True)
             x = prep(np.maximum(g.standard_normal(case.shape_x, dtype=np.float32), 0), dt)
             w = prep(g.standard_normal(case.shape_w, dtype=np.float32) * np.float32(0.05), dt)
@@ -485,12 +455,8 @@ def test_fused_relu_backward_entry_points():
             ref = oracle.conv_bwd_data(dy, w, (13, 13), 1, 1, y=yy) * (x > 0)
             ref = oracle.round_bf16(ref) if dt == "bf16" else ref
             out = empty(case.shape_x, dt)
-            if split:
-                os.environ["OWT_SPLITK"] = split
-            try:
+            with force(-1, split):
                 m.owt_conv_bwd_data_relu_in(case.desc, to_dev(dy, dt), to_dev(yy, dt), to_dev(w, dt), to_dev(x, dt), out, case.ws(1))
-            finally:
-                os.environ.pop("OWT_SPLITK", None)
             torch.cuda.synchronize()
             assert_close(to_host(out), ref, dt, "conv_bwd_data_relu_in K=%d" % K)
 
