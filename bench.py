@@ -6,16 +6,20 @@ the paper), on seeded synthetic images of the ILSVRC crop shape 224x224x3.
 A step = conv1..5 forward (bias+ReLU fused, 3 max-pools), then 3 pool-backward,
 5 backward-filter (+bias gradient) and 4 backward-data calls (the first layer's
 input is data, so its dx has no consumer).  Inputs live in HBM before the clock
-starts.  Prints ONE JSON line.
+starts.  Prints ONE JSON line: the headline workload (config 3 unless --workload
+says otherwise) with its roofline, the CPU oracle timed on the same step, the
+per-tensor error of the timed configuration against that oracle step, and -- for
+the default workload -- shorter runs of the other configurations under
+"other_workloads".
 
   python bench.py [--gpus 1] [--steps K] [--warmup W]
                   [--workload conv_stack|conv_stack_fc|conv_stack_bf16|conv_stack_paper|train_step|
-                              train_step_kpass]
+                              train_step_kpass] [--no-others]
 """
 import argparse
+import glob
 import json
 import os
-import re
 import sys
 import time
 
@@ -33,19 +37,385 @@ WORKLOADS = {
     "train_step_kpass": (4, "train_step under scheme (b) of Section 4 with K = 8: conv stack on the own 128 images, eight "
                             "fwd+bwd iterations of the FC shards (own batch + 7 seeded peer batches), update; fp32"),
 }
+OTHERS = ("conv_stack_bf16", "conv_stack_fc", "train_step", "train_step_kpass", "conv_stack_paper")
+
+
+def gpu_clocks():
+    """Current shader / memory clock of every card as the driver's sysfs files show them (the line marked
+    '*'); None when they cannot be read.  Read before and after the timed region: the clocks are as found."""
+    out = {}
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk") + glob.glob("/sys/class/drm/card*/device/pp_dpm_mclk")):
+        try:
+            cur = [ln.split(":", 1)[1].strip().rstrip("*").strip() for ln in open(path) if ln.strip().endswith("*")]
+        except OSError:
+            continue
+        if cur:
+            out["%s %s" % (path.split("/")[4], path.rsplit("_", 1)[1])] = cur[0]
+    return out or None
+
+
+def stats(ms):
+    import numpy as np
+    a = np.sort(np.asarray(ms, dtype=np.float64))
+    return {"median": round(float(np.median(a)), 4), "min": round(float(a[0]), 4), "max": round(float(a[-1]), 4), "n": int(a.size)}
+
+
+class Workload:
+    """One configuration set up on the GPU: the stack, its seeded inputs, and what one step is."""
+
+    def __init__(self, name, args):
+        import numpy as np
+        import torch
+        import synthetic_inputs as si
+        from paper_1404_5997_amd.stack import ConvStack
+        self.name, self.args = name, args
+        self.dt = dt = "bf16" if name == "conv_stack_bf16" else "f32"
+        self.N = N = 1024 if dt == "bf16" else 128
+        self.cfg, self.title = WORKLOADS[name]
+        cfg = self.cfg
+        self.filters = filters = si.PAPER_FILTERS if name == "conv_stack_paper" else None
+        self.layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
+        self.kpass = name == "train_step_kpass"
+        self.with_fc = name in ("conv_stack_fc", "train_step", "train_step_kpass")
+        self.train = name in ("train_step", "train_step_kpass")
+
+        def rnd(a):   # bf16 workloads: make the seeded inputs bf16-representable (input preparation only)
+            return a if dt != "bf16" else torch.from_numpy(a).to(torch.bfloat16).float().numpy()
+
+        self.st = st = ConvStack(N, self.layers, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
+                                 fc_layers=si.FC_LAYERS if self.with_fc else None, fc_workers=si.FC_WORKERS)
+        self.x = rnd(si.stack_input(cfg, N))
+        ws, self.bs = si.stack_params(cfg, filters)
+        self.ws = [rnd(w) for w in ws]
+        if self.with_fc:
+            self.fws, self.fbs = si.fc_params(cfg)
+            self.peers = [si.fc_peer_columns(cfg, i, N) for i in range(2)]
+            st.load(self.x, self.ws, self.bs, self.fws, self.fbs, self.peers)
+        else:
+            st.load(self.x, self.ws, self.bs)
+        self.g = rnd(si.upstream_grad(cfg, 90, tuple(st.top_grad().shape)))
+        st.top_grad().copy_(torch.from_numpy(self.g).to(st.tdt))
+        if self.train:     # seeded class labels; momentum 0.9, learning rate 0.01, weight decay 0.0005 (Section 5's example)
+            self.labels_host = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 95).integers(0, 1000, size=N).astype(np.int32)
+            st.set_labels(self.labels_host)
+        self.KW = si.FC_WORKERS
+        if self.kpass:     # what the other K-1 workers would broadcast: seeded activations of the last-stage shape, and labels
+            gk = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 96)
+            self.peer_feats = [torch.from_numpy(np.maximum(gk.standard_normal((N, st.F[0]["I"]), dtype=np.float32), 0) * np.float32(0.05)).cuda()
+                               for _ in range(self.KW - 1)]
+            self.klabels = [torch.from_numpy(gk.integers(0, 1000, size=N).astype(np.int32)).cuda() for _ in range(self.KW)]
+        self.conv_flops, self.fc_flops = st.conv_flops(), st.fc_flops()
+        self.fc_total = self.fc_flops * (si.FC_WORKERS if self.kpass else 1)
+        if not args.no_autotune:
+            st.autotune()      # set-up, outside the timed region: the library times its variants per layer
+        torch.cuda.synchronize()
+
+    def one_step(self, per_pass=None, overlap=None):
+        st = self.st
+        if self.kpass:
+            st.step_kpass(self.peer_feats, self.klabels, per_pass, self.args.kpass_overlap if overlap is None else overlap)
+            st.update(0.9, 0.01, 0.0005, part="conv" if per_pass else "all")
+            return
+        st.step()
+        if self.train:
+            st.update(0.9, 0.01, 0.0005)
+
+    def time_steps(self, steps, warmup, **kw):
+        """W untimed steps, then exactly K steps between two synchronisations (wall clock), each step also
+        bracketed by HIP events on the launch stream (torch's current stream is the one the binding
+        passes to the library).  Returns (wall ms per step, per-step event durations in ms)."""
+        import torch
+        for _ in range(warmup):
+            self.one_step(**kw)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev[0].record()
+        for i in range(steps):
+            self.one_step(**kw)
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / steps, [ev[i].elapsed_time(ev[i + 1]) for i in range(steps)]
+
+    def per_call(self, reps):
+        """Duration of every library call of a step (HIP events around each call, mean over reps), in ms."""
+        import numpy as np
+        import torch
+        recs = {}
+
+        def hook(tag, thunk):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); thunk(); b.record()
+            recs.setdefault(tag, []).append((a, b))
+
+        self.st.hook = hook
+        for _ in range(reps):    # (the K-pass workload is broken down as one plain step + update)
+            self.st.step()
+            if self.train:
+                self.st.update(0.9, 0.01, 0.0005)
+        torch.cuda.synchronize()
+        self.st.hook = None
+        return {tag: float(np.mean([a.elapsed_time(b) for a, b in evs])) for tag, evs in recs.items()}
+
+    def kernel_groups(self, per_call):
+        """Convolution calls grouped by the kernel that serves them: the library's description of the chosen
+        variant without its split count and grid, so that launches of ONE kernel template with different
+        split counts (conv3/4/5 filter gradients) fall into one group."""
+        import re
+        import paper_1404_5997_amd as owt
+        groups = {}
+        for li, e in enumerate(self.st.L):
+            Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+            fl = 2.0 * Nn * P * Q * K * R * R * C
+            for ps, pname in ((0, "fwd"), (1, "bwd_data"), (2, "bwd_filter")):
+                tag = "conv%d %s" % (li + 1, pname)
+                if tag not in per_call:
+                    continue
+                d = e["desc"] if ps == 0 or not e["dz_ready"] else e["desc_bwd"]
+                full = owt.owt_conv_plan_describe(d, ps)
+                variant = re.sub(r" splitk\d+", "", full.rsplit(" grid", 1)[0])
+                gk = groups.setdefault(variant, dict(ms=0.0, flops=0.0, launches=0, calls=[], plans=[]))
+                gk["ms"] += per_call[tag]; gk["flops"] += fl; gk["launches"] += 1; gk["calls"].append(tag)
+                gk["plans"].append(full)
+        return groups
+
+    def roofline(self, per_call, groups):
+        dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
+        achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
+        # HBM bytes per launch of that kernel, from the committed counter summary (profiles/hbm_traffic.json:
+        # FETCH_SIZE / WRITE_SIZE per dispatch of the same calls, scaled by what a plain copy of known size reads)
+        traffic, traffic_kernel = None, None
+        tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+        if os.path.exists(tpath):
+            table_t = json.load(open(tpath)).get(self.name, {})
+            ck = ["call " + c for c in dom["calls"]]
+            if all(k in table_t for k in ck):
+                traffic = round(sum(table_t[k]["fetch_bytes"] + table_t[k]["write_bytes"] for k in ck) / len(ck))
+                traffic_kernel = sorted(set(table_t[k].get("kernel", "?") for k in ck))
+        r = {"bound": "mfma", "kernel": dom_name, "calls": dom["calls"], "launches_per_step": dom["launches"],
+             "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
+             "gflop_per_launch": round(dom["flops"] / dom["launches"] / 1e9, 3),
+             "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[self.dt], "unit": "TFLOP/s",
+             "frac": round(achieved / PEAK_TFLOPS[self.dt], 4), "traffic": traffic}
+        if traffic_kernel:
+            r["traffic_kernel"] = traffic_kernel
+        return r
+
+    def hbm_kernels(self, per_call):
+        """The HBM-bound kernels of the step: algorithmic bytes (each operand once) over the measured duration."""
+        st, esz, hbm = self.st, (2 if self.dt == "bf16" else 4), {}
+        for li, e in enumerate(st.L):
+            if e["pool"]:
+                Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
+                big, small = Nn * P * Q * K, e["a"].numel()
+                hbm["pool%d fwd" % (li + 1)] = big * esz + small * (esz + 1)             # read y; write pooled + arg-max
+                hbm["pool%d bwd" % (li + 1)] = small * (2 * esz + 1) + big * esz         # read dy, pooled y, arg-max; write dx
+        if self.train:
+            hbm["sgd update all"] = st.n_params * 20                                         # read w, vel, g; write w, vel
+        return {k: {"bytes": b, "ms": round(per_call[k], 4), "GB/s": round(b / per_call[k] / 1e6, 1),
+                    "frac_of_8TB/s": round(b / per_call[k] / 1e6 / 8000.0, 4)} for k, b in hbm.items() if k in per_call}
+
+    def kpass_schedule(self, steps):
+        """The four ways to run the K iterations, same work each: ms per step (median of HIP-event step times)."""
+        upd = (0.9, 0.01, 0.0005)
+        out = {"K": self.KW, "fc_gflop_per_step": round(self.fc_flops * self.KW / 1e9, 2)}
+        for key, kw in (("accumulate_serial_ms", dict(per_pass=None, overlap=False)),
+                        ("accumulate_overlap_ms", dict(per_pass=None, overlap=True)),
+                        ("update_every_pass_serial_ms", dict(per_pass=upd, overlap=False)),
+                        ("update_every_pass_overlap_ms", dict(per_pass=upd, overlap=True))):
+            _, ev = self.time_steps(steps, 3, **kw)
+            out[key] = stats(ev)["median"]
+        return out
+
+    # ------------------------------------------------------------------ CPU oracle on the same step
+    def oracle_step(self, n_images):
+        """The oracle (as it stands: direct loops, double accumulators) on the step's first n_images images,
+        timed, and -- when that is the whole batch of a workload without weight update -- every tensor of the
+        GPU's step compared with it.  Forward runs free from the images.  The backward calls are given the GPU's
+        forward outputs as ReLU masks and the GPU's pooling arg-max as inputs (fetched before the clock
+        starts): ReLU and arg-max are not smooth, and an element that is +1e-9 on one side and 0 on the other
+        would otherwise move gradients by more than rounding; the work timed is the same."""
+        import numpy as np
+        import oracle
+        import synthetic_inputs as si
+        st, n, N = self.st, min(n_images, self.N), self.N
+        layers, ws, bs = self.layers, self.ws, self.bs
+        compare = n == N and not self.train and self.dt == "f32"
+        host = lambda t: t.float().cpu().numpy()
+        gy = [host(e["y"][:n]) for e in st.L] if compare else None
+        gam = [e["am"][:n].cpu().numpy() if e["pool"] else None for e in st.L] if compare else None
+        parity = {}
+
+        def cmp(tag, gpu_t, ref):
+            if compare:
+                g = host(gpu_t)
+                parity[tag] = float("%.3e" % (np.max(np.abs(g.astype(np.float64) - ref)) / max(np.max(np.abs(ref)), 1e-300)))
+
+        xs, gs = self.x[:n], self.g[:n]
+        t0 = time.perf_counter()
+        acts, cur = [], xs
+        for li, L in enumerate(layers):
+            y = oracle.conv_fwd(cur, ws[li], bs[li], L["stride"], L["pad"], True)
+            rec = dict(x=cur, y=y)
+            cur = y
+            if L["pool"]:
+                cur, rec["am"] = oracle.maxpool_fwd(y, si.POOL_WIN, si.POOL_STRIDE)
+                rec["a"] = cur
+            acts.append(rec)
+        what = "conv stack fwd+bwd"
+        fcrec = None
+        if not self.with_fc:
+            grad = gs
+        else:     # the worker's dense shards (own columns beside the peers' seeded columns), as the GPU step does
+            what = "conv stack + FC shards fwd+bwd" + (" + logistic output + update" if self.train else "")
+            fws, fbs, peers = self.fws, self.fbs, self.peers
+            feats, fin, fout = cur.reshape(n, -1), [], []
+            for i, spec in enumerate(si.FC_LAYERS):
+                if i > 0:
+                    feats = np.concatenate([fout[-1], peers[i - 1][:n]], axis=1)
+                fin.append(feats)
+                fout.append(oracle.fc_fwd(feats, fws[i], fbs[i], spec["relu"]))
+            dtop = oracle.logistic_xent(fout[-1], self.labels_host[:n], 0, 1.0)[1] if self.train else gs
+            fgrads = [None] * len(si.FC_LAYERS)
+            for i in range(len(si.FC_LAYERS) - 1, -1, -1):
+                ymask = (host(st.F[i]["y"][:n]) if compare else fout[i]) if si.FC_LAYERS[i]["relu"] else None
+                dxp, dwf, dbf = oracle.fc_bwd(fin[i], fws[i], dtop, y=ymask, alpha=1.0 / n)
+                fgrads[i] = (dxp, dwf, dbf)
+                if self.train:
+                    oracle.sgd_momentum(fws[i], np.zeros_like(fws[i]), dwf, 0.9, 0.01, 0.0005, -1.0)
+                dtop = dxp[:, :fout[i - 1].shape[1]] if i > 0 else dxp
+            grad = dtop.reshape(cur.shape)
+            fcrec = (fout, fgrads)
+        back = [None] * len(layers)
+        for li in range(len(layers) - 1, -1, -1):
+            L, rec = layers[li], acts[li]
+            ymask = gy[li] if compare else rec["y"]
+            if L["pool"]:
+                grad = oracle.maxpool_bwd(grad, gam[li] if compare else rec["am"], rec["y"].shape[1:3], si.POOL_WIN, si.POOL_STRIDE)
+            dwc, dbc = oracle.conv_bwd_filter(rec["x"], grad, (L["R"], L["R"]), L["stride"], L["pad"], y=ymask, alpha=1.0 / n)
+            if self.train:
+                oracle.sgd_momentum(ws[li], np.zeros_like(ws[li]), dwc, 0.9, 0.01, 0.0005, -1.0)
+            back[li] = (grad, dwc, dbc)
+            if li > 0:
+                grad = oracle.conv_bwd_data(grad, ws[li], rec["x"].shape[1:3], L["stride"], L["pad"], y=ymask)
+        dtc = time.perf_counter() - t0
+        cpu = {"value": round(n / dtc, 3), "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
+               "sample": "%s (fp32 in, double accumulate) on %d of the %d images, %.1f s" % (what, n, N, dtc)}
+        if compare:     # max |gpu - oracle| / max |oracle| per tensor of the timed configuration
+            for li, (e, rec) in enumerate(zip(st.L, acts)):
+                cmp("conv%d y" % (li + 1), e["y"], rec["y"])
+                if e["pool"]:
+                    cmp("pool%d a" % (li + 1), e["a"], rec["a"])
+                grad, dwc, dbc = back[li]
+                cmp("conv%d dz" % (li + 1), e["dy"], grad * (gy[li] > 0))
+                cmp("conv%d dw" % (li + 1), e["dw"], dwc)
+                cmp("conv%d db" % (li + 1), e["db"], dbc)
+            if fcrec:
+                for i, f in enumerate(st.F):
+                    cmp("fc%d y" % (i + 1), f["y"], fcrec[0][i])
+                    cmp("fc%d dx_partial" % (i + 1), f["dx"].reshape(fcrec[1][i][0].shape), fcrec[1][i][0])
+                    cmp("fc%d dw" % (i + 1), f["dw"], fcrec[1][i][1])
+                    cmp("fc%d db" % (i + 1), f["db"], fcrec[1][i][2])
+            worst = max(parity.values())
+            parity = {"tolerance": 1e-4, "max_rel_err": worst, "ok": bool(worst <= 1e-4), "images": n,
+                      "what": "max|gpu - oracle| / max|oracle| per tensor; tuned variants, as timed", "tensors": parity}
+        return cpu, (parity if compare else None)
+
+
+def run_workload(name, args, steps, warmup, per_call_reps, headline):
+    import torch
+    w = Workload(name, args)
+    clocks0 = gpu_clocks() if headline else None
+    ms_wall, ev = w.time_steps(steps, warmup)
+    clocks1 = gpu_clocks() if headline else None
+    st_ev = stats(ev)
+    ms = ms_wall if headline else st_ev["median"]
+    tflops = (w.conv_flops + w.fc_total) / (ms * 1e-3) / 1e12
+    per_call = w.per_call(per_call_reps)
+    groups = w.kernel_groups(per_call)
+    out = {"workload": w.title, "dtype": w.dt, "batch": w.N, "ms_per_step": round(ms, 4), "step_ms_hip_events": st_ev,
+           "images_per_s": round(w.N / (ms * 1e-3), 2), "tflops": round(tflops, 3),
+           "frac_of_mfma_peak": round(tflops / PEAK_TFLOPS[w.dt], 4),
+           "conv_gflop_per_step": round(w.conv_flops / 1e9, 2), "fc_gflop_per_step": round(w.fc_total / 1e9, 2),
+           "roofline": w.roofline(per_call, groups), "hbm_kernels": w.hbm_kernels(per_call)}
+    if w.with_fc:      # the dense shards reported apart from the convolution stack
+        fc_ms = sum(v for k, v in per_call.items() if k.startswith("fc"))
+        out["fc_shards"] = {"us_per_fwd_bwd_iteration": round(fc_ms * 1e3, 1), "gflop": round(w.fc_flops / 1e9, 3),
+                            "tflops": round(w.fc_flops / (fc_ms * 1e-3) / 1e12, 2),
+                            "calls_us": {k: round(v * 1e3, 1) for k, v in per_call.items() if k.startswith("fc")}}
+    if w.kpass:
+        out["kpass_schedule"] = w.kpass_schedule(max(10, steps // 2))
+    if headline:
+        out["per_call_ms"] = {tag: round(v, 4) for tag, v in per_call.items()}
+        out["kernel_variants"] = {k: {"calls": v["calls"], "plans": v["plans"], "ms": round(v["ms"], 4),
+                                      "tflops": round(v["flops"] / v["ms"] / 1e9, 2)} for k, v in groups.items()}
+        out["clocks"] = {"before": clocks0, "after": clocks1}
+    if args.table:
+        for tag, v in sorted(per_call.items(), key=lambda kv: -kv[1]):
+            print("%-20s %8.3f ms" % (tag, v), file=sys.stderr)
+        for k, v in groups.items():
+            print("%-72s %8.3f ms  %7.2f TFLOP/s" % (k, v["ms"], v["flops"] / v["ms"] / 1e9), file=sys.stderr)
+    cpu = parity = None
+    if headline and not args.no_cpu_baseline:
+        w.st.step()                      # the buffers hold exactly one plain step's results
+        torch.cuda.synchronize()
+        cpu, parity = w.oracle_step(args.cpu_sample_images)
+    del w
+    torch.cuda.empty_cache()
+    return out, cpu, parity
+
+
+def run_config2(reps=50):
+    """Config 2: one mid-stack layer at batch 128 (13x13x192 -> 384 filters 3x3), its three passes timed
+    separately with HIP events (tuned variants), 28.7 GFLOP each."""
+    import torch
+    import synthetic_inputs as si
+    import paper_1404_5997_amd as owt
+    geom, x, w, b, dy = si.config2(128)
+    N, C, H, W, K, R, S = (geom[k] for k in "NCHWKRS")
+    d = owt.conv_desc(N, C, H, W, K, R, S, geom["stride"], geom["pad"], owt.OWT_F32, owt.OWT_BIAS | owt.OWT_RELU)
+    dev = lambda a: torch.from_numpy(a).cuda()
+    xd, wd, bd, dyd = dev(x), dev(w), dev(b), dev(dy)
+    y = torch.empty((N, H, W, K), device="cuda"); dx = torch.empty_like(xd); dw = torch.empty_like(wd); db = torch.empty_like(bd)
+    ws = torch.empty(max(16, max(owt.owt_conv_workspace_bytes(d, p) for p in range(3))), dtype=torch.uint8, device="cuda")
+    owt.owt_conv_fwd(d, xd, wd, bd, y, ws)
+    for p in range(3):
+        owt.owt_conv_autotune(d, p, xd, wd, bd, y, dyd, dx, dw, db, ws)
+    calls = {"fwd": lambda: owt.owt_conv_fwd(d, xd, wd, bd, y, ws),
+             "bwd_data": lambda: owt.owt_conv_bwd_data(d, dyd, y, wd, dx, ws),
+             "bwd_filter": lambda: owt.owt_conv_bwd_filter(d, xd, dyd, y, 1.0 / N, 0.0, dw, db, ws)}
+    flop = 2.0 * N * H * W * K * R * S * C
+    out = {"workload": "config 2: one layer 13x13x192 -> 384 filters 3x3, fp32, batch 128; each pass timed separately",
+           "gflop_per_pass": round(flop / 1e9, 2)}
+    for pi, (pname, fn) in enumerate(calls.items()):
+        for _ in range(5):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        s = stats([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)])
+        out[pname] = {"ms": s, "tflops": round(flop / (s["median"] * 1e-3) / 1e12, 2),
+                      "frac_of_mfma_peak": round(flop / (s["median"] * 1e-3) / 1e12 / PEAK_TFLOPS["f32"], 4),
+                      "plan": owt.owt_conv_plan_describe(d, pi)}
+    return out
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="conv_stack", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-images", type=int, default=128)
     ap.add_argument("--per-call-reps", type=int, default=10)
     ap.add_argument("--table", action="store_true", help="also print the per-call table to stderr")
     ap.add_argument("--no-autotune", action="store_true", help="let the cost model pick kernel variants")
+    ap.add_argument("--no-others", action="store_true", help="headline workload only (no other_workloads)")
     ap.add_argument("--kpass-overlap", action="store_true",
                     help="train_step_kpass: run the FC iterations on the peers' batches on a second stream")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -56,239 +426,32 @@ def main():
               "--gpus %d is not supported." % args.gpus, file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
-    import synthetic_inputs as si
-    import paper_1404_5997_amd as owt
-    from paper_1404_5997_amd.stack import ConvStack
-
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    dt = "bf16" if args.workload == "conv_stack_bf16" else "f32"
-    N = 1024 if dt == "bf16" else 128
-    cfg, workload_name = WORKLOADS[args.workload]
-    filters = si.PAPER_FILTERS if args.workload == "conv_stack_paper" else None
-    layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
-    kpass = args.workload == "train_step_kpass"
-    with_fc = args.workload in ("conv_stack_fc", "train_step", "train_step_kpass")
-    train = args.workload in ("train_step", "train_step_kpass")
 
-    def rnd(a):   # bf16 workloads: make the seeded inputs bf16-representable (input preparation only)
-        return a if dt != "bf16" else torch.from_numpy(a).to(torch.bfloat16).float().numpy()
-
-    st = ConvStack(N, layers, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
-                   fc_layers=si.FC_LAYERS if with_fc else None, fc_workers=si.FC_WORKERS)
-    x = rnd(si.stack_input(cfg, N))
-    ws, bs = si.stack_params(cfg, filters)
-    ws = [rnd(w) for w in ws]
-    if with_fc:
-        fws, fbs = si.fc_params(cfg)
-        peers = [si.fc_peer_columns(cfg, i, N) for i in range(2)]
-        st.load(x, ws, bs, fws, fbs, peers)
-    else:
-        st.load(x, ws, bs)
-    g = rnd(si.upstream_grad(cfg, 90, tuple(st.top_grad().shape)))
-    st.top_grad().copy_(torch.from_numpy(g).to(st.tdt))
-    if train:     # seeded class labels; momentum 0.9, learning rate 0.01, weight decay 0.0005 (Section 5's example)
-        labels_host = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 95).integers(0, 1000, size=N).astype(np.int32)
-        st.set_labels(labels_host)
-
-    KW = si.FC_WORKERS
-    if kpass:     # what the other K-1 workers would broadcast: seeded activations of the last-stage shape, and labels
-        gk = np.random.default_rng(si.BASE_SEED + 1000 * cfg + 96)
-        peer_feats = [torch.from_numpy(np.maximum(gk.standard_normal((N, st.F[0]["I"]), dtype=np.float32), 0) * np.float32(0.05)).cuda()
-                      for _ in range(KW - 1)]
-        klabels = [torch.from_numpy(gk.integers(0, 1000, size=N).astype(np.int32)).cuda() for _ in range(KW)]
-
-    def one_step(per_pass=None, overlap=args.kpass_overlap):
-        if kpass:
-            st.step_kpass(peer_feats, klabels, per_pass, overlap)
-            st.update(0.9, 0.01, 0.0005, part="conv" if per_pass else "all")
-            return
-        st.step()
-        if train:
-            st.update(0.9, 0.01, 0.0005)
-    if not args.no_autotune:
-        st.autotune()      # set-up, outside the timed region: the library times its variants per layer
-    torch.cuda.synchronize()
-
-    # ---------------------------------------------------------------- timed region
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        one_step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    images_per_s = N / (ms_per_step * 1e-3)
-    conv_flops, fc_flops = st.conv_flops(), st.fc_flops()
-    if kpass:
-        fc_total = fc_flops * si.FC_WORKERS
-    else:
-        fc_total = fc_flops
-    tflops = (conv_flops + fc_total) / (ms_per_step * 1e-3) / 1e12
-
-    # ------------------------------------------------- per-call durations (HIP events)
-    # Events are recorded on torch's current stream, which is the stream the binding launches on.
-    recs = {}
-
-    def hook(tag, thunk):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record(); thunk(); b.record()
-        recs.setdefault(tag, []).append((a, b))
-
-    st.hook = hook
-    for _ in range(args.per_call_reps):    # (the K-pass workload is broken down as one plain step + update)
-        st.step()
-        if train:
-            st.update(0.9, 0.01, 0.0005)
-    torch.cuda.synchronize()
-    st.hook = None
-
-    schedule = None
-    if kpass:    # the four ways to run the K iterations, same work each: ms per step
-        def timed(**kw):
-            for _ in range(3):
-                one_step(**kw)
-            torch.cuda.synchronize()
-            ta = time.perf_counter()
-            for _ in range(args.steps):
-                one_step(**kw)
-            torch.cuda.synchronize()
-            return round((time.perf_counter() - ta) * 1e3 / args.steps, 4)
-        upd = (0.9, 0.01, 0.0005)
-        schedule = {"K": KW, "fc_gflop_per_step": round(fc_flops * KW / 1e9, 2),
-                    "accumulate_serial_ms": timed(per_pass=None, overlap=False),
-                    "accumulate_overlap_ms": timed(per_pass=None, overlap=True),
-                    "update_every_pass_serial_ms": timed(per_pass=upd, overlap=False),
-                    "update_every_pass_overlap_ms": timed(per_pass=upd, overlap=True)}
-    per_call = {tag: float(np.mean([a.elapsed_time(b) for a, b in evs])) for tag, evs in recs.items()}   # ms
-
-    # group the convolution calls by the kernel variant the library runs for them
-    groups = {}
-    for li, e in enumerate(st.L):
-        Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
-        fl = 2.0 * Nn * P * Q * K * R * R * C
-        for ps, pname in ((0, "fwd"), (1, "bwd_data"), (2, "bwd_filter")):
-            tag = "conv%d %s" % (li + 1, pname)
-            if tag not in per_call:
-                continue
-            full = owt.owt_conv_plan_describe(e["desc"], ps)
-            variant = full.rsplit(" grid", 1)[0]
-            gk = groups.setdefault(variant, dict(ms=0.0, flops=0.0, launches=0, calls=[], keys=[]))
-            gk["ms"] += per_call[tag]; gk["flops"] += fl; gk["launches"] += 1; gk["calls"].append(tag)
-            gk["keys"].append("%s %s %s" % (full.split()[0], pname, re.search(r"threads(\d+)", full).group(1)))
-    dom_name, dom = max(groups.items(), key=lambda kv: kv[1]["ms"])
-    achieved = dom["flops"] / (dom["ms"] * 1e-3) / 1e12
-
-    # HBM bytes per launch of that variant, from the committed counter summary (profiles/hbm_traffic.json:
-    # FETCH_SIZE / WRITE_SIZE per dispatch, scaled by what a plain copy of known size reads), if it has them
-    traffic, traffic_kernel = None, None
-    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(tpath):
-        table_t = json.load(open(tpath)).get(args.workload, {})
-        got = [table_t[k]["fetch_bytes"] + table_t[k]["write_bytes"] for k in dom["keys"] if k in table_t]
-        if len(got) == len(dom["keys"]):
-            traffic = round(sum(got) / len(got))
-        else:
-            # the tuner picked a variant the profiled run did not use: take the same calls as they were
-            # profiled (same layer passes, the kernel named in traffic_kernel)
-            ck = ["call " + c for c in dom["calls"]]
-            if all(k in table_t for k in ck):
-                traffic = round(sum(table_t[k]["fetch_bytes"] + table_t[k]["write_bytes"] for k in ck) / len(ck))
-                traffic_kernel = sorted(set(table_t[k].get("kernel", "?") for k in ck))
-    roofline = {"bound": "mfma", "kernel": dom_name, "calls": dom["calls"],
-                "avg_launch_ms": round(dom["ms"] / dom["launches"], 4),
-                "achieved": round(achieved, 3), "peak": PEAK_TFLOPS[dt], "unit": "TFLOP/s",
-                "frac": round(achieved / PEAK_TFLOPS[dt], 4), "traffic": traffic}
-    if traffic_kernel:
-        roofline["traffic_kernel"] = traffic_kernel
-
-    # the HBM-bound kernels of the step: algorithmic bytes (each operand once) over the measured duration
-    esz = 2 if dt == "bf16" else 4
-    hbm = {}
-    for li, e in enumerate(st.L):
-        if e["pool"]:
-            Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
-            big, small = Nn * P * Q * K, e["a"].numel()
-            hbm["pool%d fwd" % (li + 1)] = big * esz + small * (esz + 1)             # read y; write pooled + arg-max
-            hbm["pool%d bwd" % (li + 1)] = small * (2 * esz + 1) + big * esz         # read dy, pooled y, arg-max; write dx
-    if train:
-        hbm["sgd update all"] = st.n_params * 20                                         # read w, vel, g; write w, vel
-    hbm_kernels = {k: {"bytes": b, "ms": round(per_call[k], 4), "GB/s": round(b / per_call[k] / 1e6, 1),
-                       "frac_of_8TB/s": round(b / per_call[k] / 1e6 / 8000.0, 4)} for k, b in hbm.items() if k in per_call}
-
-    # ------------------------------------------------------------------ CPU baseline
-    cpu = None
-    if not args.no_cpu_baseline:
-        import oracle
-        n = min(args.cpu_sample_images, N)
-        xs, gs = x[:n], g[:n]
-        t0 = time.perf_counter()
-        acts, cur = [], xs
-        for li, L in enumerate(layers):
-            y = oracle.conv_fwd(cur, ws[li], bs[li], L["stride"], L["pad"], True)
-            rec = dict(x=cur, y=y)
-            cur = y
-            if L["pool"]:
-                cur, rec["am"] = oracle.maxpool_fwd(y, si.POOL_WIN, si.POOL_STRIDE)
-            acts.append(rec)
-        what = "conv stack fwd+bwd"
-        if not with_fc:
-            grad = gs
-        else:     # the worker's dense shards (own columns beside the peers' seeded columns), as the GPU step does
-            what = "conv stack + FC shards fwd+bwd" + (" + logistic output + update" if train else "")
-            feats, fin, fout = cur.reshape(n, -1), [], []
-            for i, spec in enumerate(si.FC_LAYERS):
-                if i > 0:
-                    feats = np.concatenate([fout[-1], peers[i - 1][:n]], axis=1)
-                fin.append(feats)
-                fout.append(oracle.fc_fwd(feats, fws[i], fbs[i], spec["relu"]))
-            if train:
-                _, dtop = oracle.logistic_xent(fout[-1], labels_host[:n], 0, 1.0)
-            else:
-                dtop = gs
-            for i in range(len(si.FC_LAYERS) - 1, -1, -1):
-                dxp, dwf, dbf = oracle.fc_bwd(fin[i], fws[i], dtop, y=fout[i] if si.FC_LAYERS[i]["relu"] else None,
-                                              alpha=1.0 / n)
-                if train:
-                    oracle.sgd_momentum(fws[i], np.zeros_like(fws[i]), dwf, 0.9, 0.01, 0.0005, -1.0)
-                dtop = dxp[:, :fout[i - 1].shape[1]] if i > 0 else dxp
-            grad = dtop.reshape(cur.shape)
-        for li in range(len(layers) - 1, -1, -1):
-            L, rec = layers[li], acts[li]
-            if L["pool"]:
-                grad = oracle.maxpool_bwd(grad, rec["am"], rec["y"].shape[1:3], si.POOL_WIN, si.POOL_STRIDE)
-            dwc, dbc = oracle.conv_bwd_filter(rec["x"], grad, (L["R"], L["R"]), L["stride"], L["pad"], y=rec["y"], alpha=1.0 / n)
-            if train:
-                oracle.sgd_momentum(ws[li], np.zeros_like(ws[li]), dwc, 0.9, 0.01, 0.0005, -1.0)
-            if li > 0:
-                grad = oracle.conv_bwd_data(grad, ws[li], rec["x"].shape[1:3], L["stride"], L["pad"], y=rec["y"])
-        dtc = time.perf_counter() - t0
-        cpu = {"value": round(n / dtc, 3), "unit": "images/s", "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": "%s (fp32 in, double accumulate) on %d of the %d images, %.1f s" % (what, n, N, dtc)}
+    head, cpu, parity = run_workload(args.workload, args, args.steps, args.warmup, args.per_call_reps, True)
+    others = None
+    if args.workload == "conv_stack" and not args.no_others:
+        others = {"config2_single_layer": run_config2()}
+        for name in OTHERS:
+            o, _, _ = run_workload(name, args, min(args.steps, 30), min(args.warmup, 5), max(3, args.per_call_reps // 2), False)
+            others[name] = o
 
     out = {
         "metric": "conv-stack fwd+bwd images/sec at batch 128; TFLOP/s as % MFMA peak",
-        "value": round(images_per_s, 2), "unit": "images/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": dt, "data": "synthetic",
-        "config": {"workload": workload_name, "batch": N, "conv_gflop_per_step": round(conv_flops / 1e9, 2),
-                   "fc_gflop_per_step": round(fc_total / 1e9, 2)},
-        "tflops": round(tflops, 3), "frac_of_mfma_peak": round(tflops / PEAK_TFLOPS[dt], 4),
-        "roofline": roofline, "cpu_baseline": cpu,
-        "hbm_kernels": hbm_kernels, "kpass_schedule": schedule,
-        "per_call_ms": {tag: round(ms, 4) for tag, ms in per_call.items()},
-        "kernel_variants": {k: {"calls": v["calls"], "ms": round(v["ms"], 4),
-                                "tflops": round(v["flops"] / v["ms"] / 1e9, 2)} for k, v in groups.items()},
+        "value": head["images_per_s"], "unit": "images/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": head["dtype"], "data": "synthetic",
+        "config": {"workload": head["workload"], "batch": head["batch"], "conv_gflop_per_step": head["conv_gflop_per_step"],
+                   "fc_gflop_per_step": head["fc_gflop_per_step"]},
+        "tflops": head["tflops"], "frac_of_mfma_peak": head["frac_of_mfma_peak"],
+        "step_ms_hip_events": head["step_ms_hip_events"],
+        "roofline": head["roofline"], "cpu_baseline": cpu, "parity": parity,
+        "hbm_kernels": head["hbm_kernels"], "kpass_schedule": head.get("kpass_schedule"), "fc_shards": head.get("fc_shards"),
+        "clocks": head["clocks"], "per_call_ms": head["per_call_ms"], "kernel_variants": head["kernel_variants"],
+        "other_workloads": others,
     }
-    if args.table:
-        for tag, ms in sorted(per_call.items(), key=lambda kv: -kv[1]):
-            print("%-20s %8.3f ms" % (tag, ms), file=sys.stderr)
-        for k, v in groups.items():
-            print("%-72s %8.3f ms  %7.2f TFLOP/s" % (k, v["ms"], v["flops"] / v["ms"] / 1e9), file=sys.stderr)
     if args.copy_calibration:
         a = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)   # 1 GiB: larger than the 256 MB Infinity Cache
         b = torch.empty_like(a)

@@ -84,6 +84,18 @@ def test_config2_shape_bf16_storage():
                  geom["stride"], geom["pad"], dt="bf16", tensors=(x, w, b, dy))
 
 
+@pytest.mark.parametrize("K", [384, 256])
+def test_paper_filter_count_layers_batch128(K):
+    # Section 5's footnote sizes the network at 64, 192, 384, 384, 256 filters: its fourth and fifth layers
+    # are 384 -> 384 and 384 -> 256 on 13x13 maps (reduction length 3456), shapes the benchmark
+    # configuration does not have.  All three passes, batch 128, every element.
+    x = si.normal(3, 60, (128, 13, 13, 384))
+    w = si.normal(3, 61 + K, (K, 3, 3, 384), 0.01)
+    b = si.normal(3, 62 + K, (K,), 0.01)
+    dy = si.upstream_grad(3, 63 + K, (128, 13, 13, K))
+    layer_parity(128, 384, 13, 13, K, 3, 3, 1, 1, tensors=(x, w, b, dy))
+
+
 # ------------------------------------------------------------- shape sweep ----
 
 SWEEP = [

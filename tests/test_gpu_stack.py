@@ -1,21 +1,28 @@
 """GPU parity of the chained hot path at the benchmark's full sizes and launch
-configuration: the five-layer convolution stack (configs 3 and 5) and the stack
-plus fully-connected shards (config 4).
+configuration: the five-layer convolution stack (configs 3 and 5, and the paper's
+own filter counts) and the stack plus fully-connected shards (config 4).
 
-The whole batch runs on the GPU.  The oracle cannot redo 485 GFLOP in a test, so:
- * forward: the oracle runs free on a few images (convolution, ReLU and pooling
-   act per image) and every layer's output of those images is compared;
+The whole batch runs on the GPU and the oracle redoes the WHOLE batch (a
+128-image step is a few seconds of host time), so every element of every tensor
+of the step is compared:
+ * forward: the oracle runs free from the input images and every layer's output
+   and pooled map is compared, all images;
  * pooling: the GPU's pooled maxima and arg-max must equal, bit for bit, the
    oracle's pooling of the GPU's own convolution output (all images);
- * backward-data: the oracle back-propagates the same upstream gradient through
-   the same images, using the GPU's forward outputs as ReLU masks and the GPU's
-   arg-max (both just shown valid), and every layer's dz (and dx) is compared.  ReLU and
-   arg-max are not smooth, so an element that is +1e-9 on one side and 0 on the
-   other would otherwise move gradients by far more than rounding; feeding both
-   sides the same mask makes every backward call a pure function of its inputs;
- * backward-filter: sampled entries of every layer's dw (a sum over the WHOLE
-   batch) are recomputed one by one by the oracle from the GPU's full-batch
-   inputs of that call; db likewise (all entries).
+ * backward-data: the oracle back-propagates the same upstream gradient, using
+   the GPU's forward outputs as ReLU masks and the GPU's arg-max (both just
+   shown valid), and every layer's dz (and dx) is compared, all images.  ReLU
+   and arg-max are not smooth, so an element that is +1e-9 on one side and 0 on
+   the other would otherwise move gradients by far more than rounding; feeding
+   both sides the same mask makes every backward call a pure function of its
+   inputs;
+ * backward-filter: every entry of every layer's dw and db is recomputed by the
+   oracle from the GPU's full-batch inputs of that call.
+Each check runs twice: with the variants the library's cost model picks, and
+again after ConvStack.autotune(), i.e. with the variants bench.py times.
+(`images` restricts the forward / backward-data comparison to a list of image
+blocks and dw to sampled entries: used for one of the two bf16 passes at batch
+1024, where the oracle's step takes half a minute.)
 """
 import sys
 
@@ -36,13 +43,14 @@ def say(*a):
     sys.stdout.flush()
 
 
-def build_stack(config, N, dt, with_fc=False):
+def build_stack(config, N, dt, with_fc=False, filters=None):
     from paper_1404_5997_amd.stack import ConvStack
     r = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
     x = r(si.stack_input(config, N))
-    ws, bs = si.stack_params(config)
+    ws, bs = si.stack_params(config, filters)
     ws = [r(w) for w in ws]
-    st = ConvStack(N, si.STACK_LAYERS, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
+    layers = [dict(L, K=(filters[i] if filters else L["K"])) for i, L in enumerate(si.STACK_LAYERS)]
+    st = ConvStack(N, layers, si.STACK_INPUT_HWC, (si.POOL_WIN, si.POOL_STRIDE), dt,
                    fc_layers=si.FC_LAYERS if with_fc else None, fc_workers=si.FC_WORKERS)
     fc = None
     if with_fc:
@@ -58,27 +66,43 @@ def build_stack(config, N, dt, with_fc=False):
     return st, x, ws, bs, g, fc
 
 
-def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, n_sub, n_dw_samples=96):
-    """dtop_pooled: host copy of the gradient w.r.t. the last pooled map, as the GPU backward consumed it."""
+def describe_plans(st):
+    m = __import__("paper_1404_5997_amd")
+    for li, e in enumerate(st.L):
+        d = e["desc_bwd"] if e["dz_ready"] else e["desc"]
+        say("  conv%d plans: %s | %s | %s" % (li + 1, m.owt_conv_plan_describe(e["desc"], 0).split(" grid")[0],
+                                             m.owt_conv_plan_describe(d, 1).split(" grid")[0] if li else "-",
+                                             m.owt_conv_plan_describe(d, 2).split(" grid")[0]))
+
+
+def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, images=None, n_dw_samples=96):
+    """dtop_pooled: host copy of the gradient w.r.t. the last pooled map, as the GPU backward consumed it.
+    images: None = every image and every dw entry; else a list of image indices (forward / backward-data on
+    those images only, dw sampled)."""
     N = st.N
     rnd = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
-    sub = slice(0, n_sub)
+    full = images is None
+    sub = slice(0, N) if full else np.asarray(images)
+    pick = (lambda t: to_host(t)) if full else (lambda t: to_host(t[torch.as_tensor(sub, device=t.device)]))
     win, pst = si.POOL_WIN, si.POOL_STRIDE
+    specs = [dict(stride=s["stride"], pad=s["pad"], pool=s["pool"]) for s in si.STACK_LAYERS]
 
-    # ---- forward, free-running oracle on the first n_sub images
+    # ---- forward, free-running oracle
     cur = x[sub]
     flips = []
-    for li, (e, spec) in enumerate(zip(st.L, si.STACK_LAYERS)):
+    for li, (e, spec) in enumerate(zip(st.L, specs)):
         y_ref = rnd(oracle.conv_fwd(cur, ws[li], bs[li], spec["stride"], spec["pad"], True))
-        y_gpu = to_host(e["y"][sub])
+        y_gpu = pick(e["y"])
         err = assert_close(y_gpu, y_ref, dt, "conv%d fwd" % (li + 1))
         flips.append(int(np.sum((y_gpu > 0) != (y_ref > 0))))
         cur = y_ref
         if spec["pool"]:
             a_ref, _ = oracle.maxpool_fwd(y_ref, win, pst)
-            assert_close(to_host(e["a"][sub]), a_ref, dt, "pool%d fwd" % (li + 1))
+            assert_close(pick(e["a"]), a_ref, dt, "pool%d fwd" % (li + 1))
             cur = a_ref
-        say("  conv%d fwd rel err %.2e, ReLU mask disagreements %d of %d" % (li + 1, err, flips[-1], y_ref.size))
+        say("  conv%d fwd rel err %.2e on %d images, ReLU mask disagreements %d of %d" %
+            (li + 1, err, y_ref.shape[0], flips[-1], y_ref.size))
+        del y_gpu, y_ref
 
     # ---- pooling of the GPU's own conv output: exact, all images
     for li, e in enumerate(st.L):
@@ -91,72 +115,103 @@ def check_conv_stack(st, x, ws, bs, dtop_pooled, dt, n_sub, n_dw_samples=96):
         del y_gpu, a_ref, am_ref
     say("  pooled maxima and arg-max exact on all images")
 
-    # ---- backward chain on the first n_sub images, GPU masks / arg-max as inputs.  The stack applies
-    # each layer's ReLU mask where the gradient w.r.t. that layer's output is PRODUCED (fused into the
-    # pooling backward, or into the store of the next layer's bwd-data), so every e["dy"] holds
-    # dz = dy * [y > 0]; the oracle applies the mask as its own elementwise step.
+    # ---- backward chain, GPU masks / arg-max as inputs.  The stack applies each layer's ReLU mask where the
+    # gradient w.r.t. that layer's output is PRODUCED (fused into the pooling backward, or into the store of
+    # the next layer's bwd-data), so every e["dy"] holds dz = dy * [y > 0]; the oracle applies the mask as its
+    # own elementwise step.
     g = dtop_pooled[sub]
     for li in range(len(st.L) - 1, -1, -1):
-        e, spec = st.L[li], si.STACK_LAYERS[li]
+        e, spec = st.L[li], specs[li]
         Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
-        y_mask = to_host(e["y"][sub])
+        y_mask = pick(e["y"])
         if spec["pool"]:
-            g = rnd(oracle.maxpool_bwd(g, e["am"][sub].cpu().numpy(), (P, Q), win, pst))
+            g = rnd(oracle.maxpool_bwd(g, pick(e["am"]) if not full else e["am"].cpu().numpy(), (P, Q), win, pst))
         assert e["dz_ready"]
         dz = g * (y_mask > 0)
-        err = assert_close(to_host(e["dy"][sub]), dz, dt, "conv%d dz" % (li + 1))
+        err = assert_close(pick(e["dy"]), dz, dt, "conv%d dz" % (li + 1))
+        say("  conv%d dz rel err %.2e on %d images" % (li + 1, err, dz.shape[0]))
         if li == 0:
             break
         g = rnd(oracle.conv_bwd_data(dz, ws[li], (H, W), stv, pad))
         prev = st.L[li - 1]
         if prev["pool"]:
-            err = assert_close(to_host(prev["da"][sub]), g, dt, "conv%d bwd_data" % (li + 1))
-        say("  conv%d dz rel err %.2e" % (li + 1, err))
+            err = assert_close(pick(prev["da"]), g, dt, "conv%d bwd_data" % (li + 1))
+            say("  conv%d bwd_data rel err %.2e" % (li + 1, err))
+        del y_mask, dz
 
-    # ---- backward-filter: sampled dw entries and all of db from the GPU's full-batch call inputs
+    # ---- backward-filter from the GPU's full-batch call inputs: all of dw and db (or sampled dw entries)
     rs = np.random.default_rng(123)
     for li, e in enumerate(st.L):
         Nn, C, H, W, K, R, stv, pad, P, Q = e["geom"]
-        xin, dyin, yin = to_host(e["x"]), to_host(e["dy"]), to_host(e["y"])
-        idx = np.stack([rs.integers(0, K, n_dw_samples), rs.integers(0, R, n_dw_samples),
-                        rs.integers(0, R, n_dw_samples), rs.integers(0, C, n_dw_samples)], axis=1).astype(np.int32)
-        idx[0] = (0, 0, 0, 0); idx[1] = (K - 1, R - 1, R - 1, C - 1)
-        ref = oracle.conv_bwd_filter_at(xin, dyin, idx, (R, R), stv, pad).astype(np.float64) * st.alpha   # dyin is dz
+        xin, dyin = to_host(e["x"]), to_host(e["dy"])          # dyin is dz
         dw = e["dw"].cpu().numpy()
-        got = dw[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
-        scale = np.max(np.abs(dw))          # the tensor's max norm (the sample need not contain it)
-        err = float(np.max(np.abs(got - ref)) / scale)
-        assert np.isfinite(dw).all() and err <= TOL["f32"], "conv%d dw: %.3e" % (li + 1, err)
-        # db[k] = alpha * sum dz: the dense-layer oracle on a [N*P*Q, K] matrix with a zero input column
-        rows = Nn * P * Q
-        _, _, db_ref = oracle.fc_bwd(np.zeros((rows, 1), np.float32), np.zeros((K, 1), np.float32),
-                                     dyin.reshape(rows, K), alpha=st.alpha, want_dx=False)
-        errb = assert_close(e["db"].cpu().numpy(), db_ref, "f32", "conv%d db" % (li + 1))
-        say("  conv%d dw (sampled %d) rel err %.2e, db rel err %.2e" % (li + 1, n_dw_samples, err, errb))
-        del xin, dyin, yin
+        if full:
+            dw_ref, db_ref = oracle.conv_bwd_filter(xin, dyin, (R, R), stv, pad, alpha=st.alpha)
+            err = assert_close(dw, dw_ref, "f32", "conv%d dw" % (li + 1))
+            errb = assert_close(e["db"].cpu().numpy(), db_ref, "f32", "conv%d db" % (li + 1))
+            say("  conv%d dw (all %d entries) rel err %.2e, db rel err %.2e" % (li + 1, dw.size, err, errb))
+        else:
+            idx = np.stack([rs.integers(0, K, n_dw_samples), rs.integers(0, R, n_dw_samples),
+                            rs.integers(0, R, n_dw_samples), rs.integers(0, C, n_dw_samples)], axis=1).astype(np.int32)
+            idx[0] = (0, 0, 0, 0); idx[1] = (K - 1, R - 1, R - 1, C - 1)
+            ref = oracle.conv_bwd_filter_at(xin, dyin, idx, (R, R), stv, pad).astype(np.float64) * st.alpha
+            got = dw[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]]
+            scale = np.max(np.abs(dw))          # the tensor's max norm (the sample need not contain it)
+            err = float(np.max(np.abs(got - ref)) / scale)
+            assert np.isfinite(dw).all() and err <= TOL["f32"], "conv%d dw: %.3e" % (li + 1, err)
+            # db[k] = alpha * sum dz: the dense-layer oracle on a [N*P*Q, K] matrix with a zero input column
+            rows = Nn * P * Q
+            _, _, db_ref = oracle.fc_bwd(np.zeros((rows, 1), np.float32), np.zeros((K, 1), np.float32),
+                                         dyin.reshape(rows, K), alpha=st.alpha, want_dx=False)
+            errb = assert_close(e["db"].cpu().numpy(), db_ref, "f32", "conv%d db" % (li + 1))
+            say("  conv%d dw (sampled %d) rel err %.2e, db rel err %.2e" % (li + 1, n_dw_samples, err, errb))
+        del xin, dyin
+    return flips
+
+
+def run_and_check_twice(st, x, ws, bs, dt, dtop=None, first_images=None):
+    """The step with the cost model's variants, then with the tuned ones (what bench.py times); both compared
+    with the oracle.  dtop: callable giving the host gradient of the last pooled map after a step."""
+    flips = None
+    for tuned in (False, True):
+        if tuned:
+            st.autotune()
+        st.step()
+        torch.cuda.synchronize()
+        say("%s variants:" % ("tuned" if tuned else "cost-model"))
+        describe_plans(st)
+        flips = check_conv_stack(st, x, ws, bs, dtop(), dt, images=None if tuned else first_images)
     return flips
 
 
 def test_config3_conv_stack_fp32_batch128():
     st, x, ws, bs, g, _ = build_stack(3, 128, "f32")
-    st.step()
-    torch.cuda.synchronize()
-    say("config 3: stack ran, output", st.out_shape)
     assert st.out_shape == (128, 6, 6, 256)
-    flips = check_conv_stack(st, x, ws, bs, g, "f32", n_sub=3)
-    assert sum(flips) <= 50
+    flips = run_and_check_twice(st, x, ws, bs, "f32", lambda: g)
+    total = sum(e["y"].numel() for e in st.L)
+    say("ReLU mask disagreements of the free-running forward: %d of %d" % (sum(flips), total))
+    assert sum(flips) <= 1e-5 * total
+
+
+def test_paper_filter_counts_conv_stack_fp32_batch128():
+    # the network as Section 5's footnote sizes it: 64, 192, 384, 384, 256 filters (conv4 384 -> 384 and
+    # conv5 384 -> 256, reduction length 3456 each)
+    st, x, ws, bs, g, _ = build_stack(3, 128, "f32", filters=si.PAPER_FILTERS)
+    assert st.out_shape == (128, 6, 6, 256) and st.L[3]["geom"][4] == 384 and st.L[4]["geom"][1] == 384
+    run_and_check_twice(st, x, ws, bs, "f32", lambda: g)
 
 
 def test_config5_conv_stack_bf16_batch1024():
     st, x, ws, bs, g, _ = build_stack(5, 1024, "bf16")
-    st.step()
-    torch.cuda.synchronize()
-    say("config 5: stack ran, output", st.out_shape)
-    check_conv_stack(st, x, ws, bs, g, "bf16", n_sub=2, n_dw_samples=48)
+    # cost-model variants: first, middle and last image blocks, sampled dw; tuned variants: everything
+    run_and_check_twice(st, x, ws, bs, "bf16", lambda: g, first_images=[0, 1, 511, 512, 1022, 1023])
 
 
-def test_config4_stack_plus_fc_shard_fp32():
+@pytest.mark.parametrize("tuned", [False, True])
+def test_config4_stack_plus_fc_shard_fp32(tuned):
     st, x, ws, bs, g, (fws, fbs, peers) = build_stack(4, 128, "f32", with_fc=True)
+    if tuned:
+        st.autotune()
     st.step()
     torch.cuda.synchronize()
     # every dense call against the oracle on the GPU's inputs of that call (full batch: they are small)
@@ -176,10 +231,9 @@ def test_config4_stack_plus_fc_shard_fp32():
             np.testing.assert_array_equal(xin[:, :own], to_host(st.F[i - 1]["y"]))
             np.testing.assert_array_equal(xin[:, own:], peers[i - 1])
             np.testing.assert_array_equal(to_host(st.F[i - 1]["dy"]), to_host(f["dx"])[:, :own])
-    # free-running forward of the dense part on the oracle's own conv features for a few images
-    e = st.L[-1]
-    pooled_dgrad = to_host(e["da"])           # = fc1's dx_partial, reshaped
-    check_conv_stack(st, x, ws, bs, pooled_dgrad, "f32", n_sub=2, n_dw_samples=32)
+    # the convolution part under the gradient the dense shards hand down (= fc1's dx_partial, reshaped): every
+    # image, every dw entry
+    check_conv_stack(st, x, ws, bs, to_host(st.L[-1]["da"]), "f32")
 
 
 @pytest.mark.parametrize("dt", ["f32", "bf16"])
