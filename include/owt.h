@@ -126,6 +126,21 @@ owt_status owt_conv_bwd_filter(const owt_conv_desc *d, const void *x, const void
                                const void *y_or_null, float alpha, float beta, float *dw,
                                float *dbias_or_null, void *ws, size_t ws_bytes, void *hip_stream);
 
+/* owt_conv_bwd_filter for callers that CANNOT ALLOCATE device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * result as owt_conv_bwd_filter minus ws / ws_bytes: the partial sums of the split reduction go to
+ * a static array of device memory inside the library (owt_static_scratch_bytes() = 64 MiB, one copy
+ * per GPU, held until the process ends).  The call allocates and frees nothing.  It runs the variant
+ * owt_conv_bwd_filter would run when that variant's partial sums fit the array, otherwise the
+ * cheapest variant that does (results then differ in summation order only); if none fits it returns
+ * OWT_EWORKSPACE and launches nothing.  Nothing in the array has to start at zero (every partial sum
+ * that is read was written by the same call).  All calls on one GPU share the array: calls that
+ * overlap in time on one GPU (different streams or threads) race and give wrong results; calls on
+ * one stream are ordered and safe. */
+owt_status owt_conv_bwd_filter_static(const owt_conv_desc *d, const void *x, const void *dy, const void *y_or_null,
+                                      float alpha, float beta, float *dw, float *dbias_or_null, void *hip_stream);
+size_t owt_static_scratch_bytes(void);
+
 /* Optional tuning.  Runs every kernel variant the planner knows for this pass
  * on the caller's buffers (three timed repetitions each, HIP events on
  * hip_stream), and remembers the fastest: later owt_conv_* calls in this

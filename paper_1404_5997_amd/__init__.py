@@ -27,6 +27,7 @@ EXPORTS = (
     "owt_maxpool_bwd", "owt_last_error", "owt_abi_version", "owt_selftest_host", "owt_conv_plan_describe", "owt_conv_autotune",
     "owt_conv_bwd_data_relu_in", "owt_maxpool_bwd_relu", "owt_sgd_momentum_update", "owt_scale_hyperparameters",
     "owt_logistic_xent", "owt_fc_autotune", "owt_test_force_variant",
+    "owt_conv_bwd_filter_static", "owt_static_scratch_bytes",
 )
 
 
@@ -63,6 +64,8 @@ _lib.owt_conv_bwd_data.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_conv_bwd_data_relu_in.argtypes = [_cd, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_maxpool_bwd_relu.argtypes = [_i, _i, _i, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp]
 _lib.owt_conv_bwd_filter.argtypes = [_cd, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp, _sz, _vp]
+_lib.owt_conv_bwd_filter_static.argtypes = [_cd, _vp, _vp, _vp, _f, _f, _vp, _vp, _vp]
+_lib.owt_static_scratch_bytes.restype = _sz
 _lib.owt_conv_autotune.argtypes = [_cd, _i, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_autotune.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
 _lib.owt_fc_shard_fwd.argtypes = [_fd, _vp, _vp, _vp, _vp, _vp, _sz, _vp]
@@ -178,6 +181,15 @@ def owt_conv_bwd_filter(desc, x, dy, y_or_null, alpha, beta, dw, dbias_or_null, 
     p, n = _ws(ws)
     _check(_lib.owt_conv_bwd_filter(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(y_or_null), alpha, beta,
                                     _ptr(dw), _ptr(dbias_or_null), p, n, _stream(stream)))
+
+
+def owt_conv_bwd_filter_static(desc, x, dy, y_or_null, alpha, beta, dw, dbias_or_null, stream=None):
+    _check(_lib.owt_conv_bwd_filter_static(ctypes.byref(desc), _ptr(x), _ptr(dy), _ptr(y_or_null), alpha, beta,
+                                           _ptr(dw), _ptr(dbias_or_null), _stream(stream)))
+
+
+def owt_static_scratch_bytes():
+    return _lib.owt_static_scratch_bytes()
 
 
 def owt_conv_autotune(desc, pass_, x, w, bias, y, dy, dx, dw, dbias_or_null, ws=None, stream=None):

@@ -847,6 +847,34 @@ static owt_status launch_fc_pair(const Geom &g, const FcPair &fp, GemmParams pd,
     return OWT_OK;
 }
 
+// ---------------------------------------------------------------- static scratch
+// Device memory for owt_conv_bwd_filter_static: lives in the code object, one copy per GPU that loads
+// the library, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the device address it yields (per device) is what kernels and launchers get.
+static constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+static constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static owt_status static_scratch(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(OWT_ELAUNCH, "hipGetDevice failed: %s", hipGetErrorString(e));
+    if (dev < 0 || dev >= kMaxDevices) return fail(OWT_EUNSUPPORTED, "device ordinal %d out of range", dev);
+    std::lock_guard<std::mutex> lk(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(OWT_ELAUNCH, "hipGetSymbolAddress(scratch) failed on device %d: %s", dev, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return OWT_OK;
+}
+
 }  // namespace owt
 
 using namespace owt;
@@ -967,6 +995,39 @@ owt_status owt_conv_bwd_filter(const owt_conv_desc *d, const void *x, const void
     if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
     return conv_pass(g, OWT_PASS_BWD_FILTER, d->dtype, filter_params(d, x, dy, y_or_null, alpha, beta, dw, dbias_or_null),
                      true, ws, ws_bytes, (hipStream_t)hip_stream, true);
+}
+
+size_t owt_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+owt_status owt_conv_bwd_filter_static(const owt_conv_desc *d, const void *x, const void *dy, const void *y_or_null,
+                                      float alpha, float beta, float *dw, float *dbias_or_null, void *hip_stream)
+{
+    Geom g;
+    OWT_TRY(check_conv(d, g));
+    OWT_TRY(check_ptr(x, "x")); OWT_TRY(check_ptr(dy, "dy")); OWT_TRY(check_ptr(dw, "dw"));
+    if (dbias_or_null) OWT_TRY(check_ptr(dbias_or_null, "dbias"));
+    if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
+    const PassDims dm = conv_dims(g, OWT_PASS_BWD_FILTER);
+    // the variant owt_conv_bwd_filter would run if its partial sums fit the static array, else the
+    // cheapest (by the cost model) of those that do
+    Launch l = choose(g, OWT_PASS_BWD_FILTER, d->dtype, dm, true, true);
+    if (l.ws_bytes() > kStaticScratchBytes) {
+        std::vector<Launch> c;
+        enumerate(g, OWT_PASS_BWD_FILTER, dm, true, c);
+        size_t best = c.size(), least = (size_t)-1;
+        for (size_t i = 0; i < c.size(); i++) {
+            least = c[i].ws_bytes() < least ? c[i].ws_bytes() : least;
+            if (c[i].ws_bytes() <= kStaticScratchBytes && (best == c.size() || c[i].cost < c[best].cost)) best = i;
+        }
+        if (best == c.size())
+            return fail(OWT_EWORKSPACE, "this filter gradient needs at least %zu bytes of scratch; the static buffer holds %zu "
+                        "(use owt_conv_bwd_filter with a caller workspace)", least, kStaticScratchBytes);
+        l = c[best];
+    }
+    void *ws = nullptr;
+    OWT_TRY(static_scratch(&ws));
+    return launch(g, OWT_PASS_BWD_FILTER, d->dtype, dm, filter_params(d, x, dy, y_or_null, alpha, beta, dw, dbias_or_null), l, ws,
+                  (hipStream_t)hip_stream);
 }
 
 owt_status owt_conv_autotune(const owt_conv_desc *d, int pass, const void *x, const void *w, const float *bias,

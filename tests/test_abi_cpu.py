@@ -116,3 +116,17 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode == 2
     assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_static_scratch_entry_rejects_what_does_not_fit_before_any_launch(m):
+    # owt_conv_bwd_filter_static keeps its partial sums in a 64 MiB static device array; with every candidate
+    # forced to 64 splits of a 1024 x 9216 gradient (2.4 GB of partial sums) nothing fits: clear error, no launch
+    assert m.owt_static_scratch_bytes() == 64 << 20
+    d = m.conv_desc(64, 1024, 13, 13, 1024, 3, 3, 1, 1, m.OWT_F32, 0)
+    m.owt_test_force_variant(-1, 64, 0)
+    try:
+        with pytest.raises(m.OwtError) as ei:
+            m.owt_conv_bwd_filter_static(d, 256, 512, None, 1.0, 0.0, 1024, None, 0)
+    finally:
+        m.owt_test_force_variant(-1, 0, 0)
+    assert ei.value.status == m.OWT_EWORKSPACE and "static buffer" in str(ei.value)
