@@ -31,6 +31,7 @@ def _units():
     for ps, pname in ((0, "fwd"), (1, "data")):
         units.append(("dconv16_%s.o" % pname, "dconv_bf16_inst.hip", ["-DOWT_INST_PASS=%d" % ps]))
     units.append(("fcgemm.o", "fcgemm_inst.hip", []))
+    units.append(("dfilter2.o", "dfilter2_inst.hip", []))
     units.append(("dfilter16.o", "dfilter_bf16_inst.hip", []))
     units.append(("sconv16.o", "sconv_bf16_inst.hip", []))
     units.append(("sfilter16.o", "sfilter_bf16_inst.hip", []))

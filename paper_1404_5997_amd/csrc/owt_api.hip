@@ -58,7 +58,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -152,6 +152,26 @@ static bool dfilter_fits(const Geom &g, int variant, int &taps, int &groups)
     } else {
         span += (31 / PQ + 1) * (Hp - g.P) * Wp;
     }
+    const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
+    return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
+}
+
+// The same for the kernel with the in-work-group pixel split (fp32 storage; chunks of 32*WP pixels).
+static bool dfilter2_fits(const Geom &g, int variant, int &taps, int &groups)
+{
+    const DFilter2Variant &v = kDFilter2Variants[variant];
+    if (g.bf16 || g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W || g.C % 4 || g.K % 4) return false;
+    const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q, last = 32 * v.WP - 1;
+    if (v.SW > 0) {
+        if (g.S != v.SW || g.R * g.S != v.tmax || Wp != v.WPC) return false;
+        taps = v.tmax; groups = 1;
+    } else {
+        if (g.S != v.tmax) return false;
+        taps = g.S; groups = g.R;
+    }
+    // buffer descriptors hold byte counts in 32 bits, and bit 31 of an offset marks "reads as zero"
+    if ((long)g.N * g.H * g.W * g.C * 4 >= 0x7fffffffL || (long)g.N * PQ * g.K * 4 >= 0x7fffffffL) return false;
+    const long span = last + (last / g.Q + 1) * (Wp - g.Q) + (last / PQ + 1) * (Hp - g.P) * Wp;
     const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
     return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
 }
@@ -466,6 +486,37 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             }
         }
     }
+    if (pass == OWT_PASS_BWD_FILTER && !no_direct) {
+        for (int v = 0; v < kNumDFilter2Variants; v++) {
+            int taps, groups;
+            if (force_tile >= 0 && force_tile != kDFilter2FirstTile + v) continue;
+            if (!dfilter2_fits(g, v, taps, groups)) continue;
+            const DFilter2Variant &dv = kDFilter2Variants[v];
+            const long KT = 32 * dv.WK, CT = 32, BP = 32 * dv.WP;
+            const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, BP);
+            for (long s0 : split_ladder(tm * ctl * groups, 256)) {
+                long s = s0;
+                if (force_split > 0) s = force_split < steps ? force_split : steps;
+                else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 1280)) break;
+                const long per = cdiv(steps, s), splits = cdiv(steps, per);
+                Launch l; memset(&l, 0, sizeof(l));
+                l.kind = KIND_DFILTER2; l.tile = v; l.splits = (int)splits; l.steps = (int)steps;
+                l.steps_per_split = (int)per; l.tiles_m = (int)tm; l.tiles_n = (int)(ctl * groups);
+                l.taps = taps; l.groups = groups; l.ctiles = (int)ctl;
+                if (splits > 1) {
+                    l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                    l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+                }
+                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WP, 1, (double)KT * CT * BP * taps * per, 1.3, splits,
+                                    dm.M, dm.Ncols);
+                bool dup = false;
+                for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
+                if (!dup && (l.partial_bytes <= kMaxPartialBytes || force_split > 0) &&
+                    (force_split > 0 || tm * ctl * groups * splits >= 64 || s0 == 256)) out.push_back(l);
+                if (force_split > 0) break;
+            }
+        }
+    }
     if (pass == OWT_PASS_BWD_FILTER && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA)) {
         for (int v = 0; v < kNumDFilter16Variants; v++) {
             int taps, groups;
@@ -531,7 +582,7 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
     const bool have_direct = !out.empty() && (out[0].kind == KIND_DIRECT || out[0].kind == KIND_DIRECT16);
     for (int t = 0; t < NUM_TILES && !have_direct; t++) {
         if (!vec && t != TILE_64x64) continue;
-        if (force_tile >= 16 && !out.empty()) continue;
+        if (force_tile >= kDFilter2FirstTile && !out.empty()) continue;
         if (vec && force_tile >= 0 && force_tile < NUM_TILES && t != force_tile) continue;
         const TileInfo &ti = kTiles[t];
         const long ksteps = cdiv(dm.Kd, ti.BK);
@@ -646,6 +697,10 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
         p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
         e = owt_launch_dfilter16(l.tile, p, s);
+    } else if (l.kind == KIND_DFILTER2) {
+        p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
+        p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
+        e = owt_launch_dfilter2_f32(l.tile, p, s);
     } else if (l.kind == KIND_DFILTER) {
         p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
         p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
@@ -696,6 +751,12 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
         return snprintf(buf, n, "dfilter16 %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
                         32 * v.KB * v.WK, 32 * v.WC, l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits,
                         (long)l.tiles_m * l.tiles_n * l.splits * 64 * v.WK * v.WC);
+    }
+    if (l.kind == KIND_DFILTER2) {
+        const DFilter2Variant &v = kDFilter2Variants[l.tile];
+        return snprintf(buf, n, "dfilter2 %s %s tile%dx32 pixelparts%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds, 32 * v.WK,
+                        v.WP, l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits,
+                        (long)l.tiles_m * l.tiles_n * l.splits * 64 * v.WK * v.WP);
     }
     if (l.kind == KIND_DFILTER) {
         const DFilterVariant &v = kDFilterVariants[l.tile];
