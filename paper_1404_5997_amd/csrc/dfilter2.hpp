@@ -27,6 +27,8 @@
 // have almost none:
 //  * the padded row width WPC and the filter width SW are template parameters, so the LDS address of
 //    tap (r,s) is one per-pixel base (read from a table of byte offsets) plus an immediate offset;
+//  * what the loaders need to know about a chunk (which pixel a panel row shows, where a pixel's panel row
+//    is) comes from two small LDS tables instead of divisions;
 //  * global loads are buffer loads: a thread's offsets into the dz chunk are constants, the chunk's
 //    base goes into the buffer descriptor (scalar arithmetic), and whatever must read as zero (rows past
 //    the end of the tensor, filters or channels past the end of a ragged tile, padding pixels) gets an
@@ -67,6 +69,7 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
     static_assert(TG >= 1, "LDS too small for the reduction tree");
     static_assert(ARPP * KT <= 2 * STAGE, "LDS too small for the bias-gradient sums");
     constexpr unsigned OOB = 0x80000000u;                                // a byte offset no descriptor here reaches
+    constexpr int TABMAX = 1024;                                         // entries of each of the two loader tables
 
     __shared__ __attribute__((aligned(16))) float lds[2 * STAGE];
 
@@ -96,8 +99,26 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
         return (n * p.Hp + pp) * Wp + q;
     };
 
-    // ---- loaders.  Per-thread constants: byte offsets of the thread's ANP pieces inside a dz chunk, the
-    // panel pieces it owns, and which of its pieces exist at all (ragged last filter / channel tile).
+    // ---- loaders.  Two tables in LDS, filled once, replace the per-chunk divisions (integer multiplies run at
+    // a quarter of the vector rate, and vector instructions cost matrix time here):
+    //   xoff_tab[pos], pos < Hp*Wp: byte offset inside an image of the pixel that padded position pos shows, or OOB;
+    //   prow_tab[pq],  pq < P*Q:    PB*4 times the padded position of output pixel pq's window corner.
+    // A chunk touches at most two images (host-checked: BP <= P*Q and PRF <= Hp*Wp), so a thread only has to
+    // decide which of the two it is in: compare, conditional subtract, table read.
+    __shared__ unsigned xoff_tab[TABMAX];
+    __shared__ int prow_tab[TABMAX];
+    const int IP = p.Hp * Wp, PQ = g.P * g.Q;
+    for (int pos = threadIdx.x; pos < IP; pos += NT) {
+        const int hp = p.dWp.div(pos), wp = pos - hp * Wp, h = hp - g.ph, w = wp - g.pw;
+        xoff_tab[pos] = ((unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W) ? (unsigned)((h * g.W + w) * g.C) * 4u : OOB;
+    }
+    for (int pq = threadIdx.x; pq < PQ; pq += NT) {
+        const int pp = g.dQ.div(pq), q = pq - pp * g.Q;
+        prow_tab[pq] = (pp * Wp + q) * (PB * 4);
+    }
+    __syncthreads();
+    // Per-thread constants: byte offsets of the thread's ANP pieces inside a dz chunk, the panel pieces it owns,
+    // and which of its pieces exist at all (ragged last filter / channel tile).
     const int akq = tid % KQ, arow0 = tid / KQ;
     const int bq = tid % TPR, brow0 = tid / TPR;
     unsigned avoff[ANP];
@@ -110,15 +131,21 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
     const bool c_full = c0 + CT <= g.C;   // uniform: every piece of the channel tile exists
     const __amdgpu_buffer_rsrc_t xrsrc =
         __builtin_amdgcn_make_buffer_rsrc((void *)p.b, 0, (int)((unsigned)g.N * g.H * g.W * g.C * 4u), 0x00020000);
-    const int pad_pix_total = g.N * p.Hp * Wp;
+    const unsigned img_bytes = (unsigned)(g.H * g.W * g.C) * 4u;
 
     float4 areg[ANP], breg[BNP][LPT];
     int tab_next = 0;
 
     auto load_chunk = [&](int ch) {
+        // wavefront-uniform bookkeeping of the chunk (scalar unit)
         const int pix0 = ch * BP, lim = min(pix0 + BP, npix);
-        const int ps = ppad(pix0) + r0 * Wp;
-        const int nrows = ppad(lim - 1) + (r0 + rows_g - 1) * Wp + g.S - ps;   // <= PRF (host-checked)
+        const int n0 = g.dPQ.div(pix0), pq0 = pix0 - n0 * PQ;
+        const int pp0 = g.dQ.div(pq0), q0 = pq0 - pp0 * g.Q;
+        const int pos0 = (pp0 + r0) * Wp + q0;                    // first panel row's padded position in image n0
+        const int nl = g.dPQ.div(lim - 1), pql = lim - 1 - nl * PQ;
+        const int ppl = g.dQ.div(pql), ql = pql - ppl * g.Q;
+        const int nrows = (nl - n0) * IP + (ppl + r0 + rows_g - 1) * Wp + ql + g.S - pos0;   // <= PRF (host-checked)
+        const unsigned img0 = (unsigned)n0 * img_bytes, img1 = n0 + 1 < g.N ? img0 + img_bytes : OOB;
         // dz rows pix0 .. pix0 + BP - 1: the descriptor starts at the chunk and ends with the tensor
         const unsigned left = (unsigned)(npix - pix0) * g.K * 4u;
         const __amdgpu_buffer_rsrc_t arsrc =
@@ -137,25 +164,26 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
         }
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
-            const int row = brow0 + i * BRPP, idx = ps + row;
-            // position of panel row `row` in the padded image -> the pixel it shows, or none (padding, past the rows
-            // this chunk needs, past the last image)
-            const int n = p.dHpWp.div(idx), r2 = idx - n * p.Hp * Wp;
-            const int hp = p.dWp.div(r2), wp = r2 - hp * Wp;
-            const int h = hp - g.ph, w = wp - g.pw;
-            const bool ok = row < nrows && idx < pad_pix_total && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-            const unsigned pixoff = ok ? (unsigned)(((n * g.H + h) * g.W + w) * g.C) * 4u : OOB;
+            // panel row -> padded position in image n0 or n0 + 1 -> the pixel it shows, or none (padding, past the
+            // rows this chunk needs, past the last image)
+            const int row = brow0 + i * BRPP, pos = pos0 + row;
+            const bool second = pos >= IP;
+            const unsigned t = xoff_tab[min((unsigned)pos, (unsigned)(pos - IP))];
+            const unsigned pixoff = row < nrows ? t + (second ? img1 : img0) : OOB;      // OOB + anything stays >= OOB
             if (c_full) {
+                const unsigned v0 = pixoff + (unsigned)((c0 + bq * 4) * 4);
 #pragma unroll
-                for (int j = 0; j < LPT; j++) breg[i][j] = buffer_load4(xrsrc, pixoff + (unsigned)((c0 + (bq + j * TPR) * 4) * 4));
+                for (int j = 0; j < LPT; j++) breg[i][j] = buffer_load4(xrsrc, v0 + j * TPR * 16);
             } else {
 #pragma unroll
                 for (int j = 0; j < LPT; j++) breg[i][j] = buffer_load4(xrsrc, (pixoff | bpiece[j]) >= OOB ? OOB : pixoff + bpiece[j]);
             }
         }
-        if (tid < BP) {
-            const int pix = pix0 + tid;
-            tab_next = pix < lim ? (ppad(pix) + r0 * Wp - ps) * (PB * 4) : 0;    // byte offset of the pixel's panel row
+        if (tid < BP) {       // byte offset of each pixel's panel row relative to the chunk's first
+            const int pq = pq0 + tid;
+            const bool second = pq >= PQ;
+            const int v = prow_tab[min((unsigned)pq, (unsigned)(pq - PQ))] + ((second ? IP : 0) + r0 * Wp - pos0) * (PB * 4);
+            tab_next = pix0 + tid < lim ? v : 0;
         }
     };
     float4 dbacc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -252,19 +280,23 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
 #pragma unroll
         for (int t0 = 0; t0 < TAPS; t0 += TG) {
             if (part >= stride && part < 2 * stride) {
-                float *red = lds + (size_t)(kb * stride + part - stride) * (TG * 16 * 64);
+                float *red = lds + (size_t)(kb * stride + part - stride) * (TG * 16 * 64) + lane * 4;
 #pragma unroll
                 for (int t = t0; t < (t0 + TG < TAPS ? t0 + TG : TAPS); t++)
 #pragma unroll
-                    for (int r = 0; r < 16; r++) red[((t - t0) * 16 + r) * 64 + lane] = acc[t][r];
+                    for (int r = 0; r < 16; r += 4)
+                        *(float4 *)(red + ((t - t0) * 4 + r / 4) * 256) = make_float4(acc[t][r], acc[t][r + 1], acc[t][r + 2], acc[t][r + 3]);
             }
             __syncthreads();
             if (part < stride) {
-                const float *red = lds + (size_t)(kb * stride + part) * (TG * 16 * 64);
+                const float *red = lds + (size_t)(kb * stride + part) * (TG * 16 * 64) + lane * 4;
 #pragma unroll
                 for (int t = t0; t < (t0 + TG < TAPS ? t0 + TG : TAPS); t++)
 #pragma unroll
-                    for (int r = 0; r < 16; r++) acc[t][r] += red[((t - t0) * 16 + r) * 64 + lane];
+                    for (int r = 0; r < 16; r += 4) {
+                        const float4 v = *(const float4 *)(red + ((t - t0) * 4 + r / 4) * 256);
+                        acc[t][r] += v.x; acc[t][r + 1] += v.y; acc[t][r + 2] += v.z; acc[t][r + 3] += v.w;
+                    }
             }
             __syncthreads();
         }

@@ -171,6 +171,8 @@ static bool dfilter2_fits(const Geom &g, int variant, int &taps, int &groups)
     }
     // buffer descriptors hold byte counts in 32 bits, and bit 31 of an offset marks "reads as zero"
     if ((long)g.N * g.H * g.W * g.C * 4 >= 0x7fffffffL || (long)g.N * PQ * g.K * 4 >= 0x7fffffffL) return false;
+    // the loaders' two LDS tables have 1024 entries, and a chunk (pixels and panel rows) may touch two images at most
+    if (Hp * Wp > 1024 || PQ > 1024 || 32 * v.WP > PQ || v.prf > Hp * Wp) return false;
     const long span = last + (last / g.Q + 1) * (Wp - g.Q) + (last / PQ + 1) * (Hp - g.P) * Wp;
     const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
     return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;

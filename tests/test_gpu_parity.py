@@ -178,7 +178,7 @@ def test_filter_gradient_with_the_pixel_split_inside_the_work_group(variant, spl
     # ragged filter and channel tiles, a last chunk with 41 or 1 valid pixels, masked dz, alpha / beta, no bias
     m = owt()
     with force(10 + variant, split, m.OWT_FORCE_ONLY_DIRECT):
-        shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 9, 14, 12, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25)),
+        shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 12, 21, 12, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25)),
                   ((1, 36, 13, 21, 64, 5, 5, 2), dict(bias=False))] if variant == 2 else \
                  [((4, 40, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
                   ((1, 8, 13, 13, 8, 3, 3, 1), dict(relu=False, alpha=1.0 / 3, beta=1.0)), ((7, 32, 13, 13, 64, 3, 3, 1), {}),
