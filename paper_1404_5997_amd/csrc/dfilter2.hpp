@@ -1,6 +1,6 @@
 // Direct filter-gradient kernel for stride-1 "same" convolutions (P == H, Q == W), fp32 storage and
-// fp32 MFMA, with the pixel reduction split INSIDE the work-group and as few vector-ALU instructions
-// per MFMA as the data layout allows.
+// fp32 MFMA, with the pixel reduction split INSIDE the work-group, operands streamed from global memory
+// straight into LDS, and as few vector-ALU instructions per MFMA as the data layout allows.
 //
 //   dw[k][r][s][c] = sum over pixels (n,p,q) of dz[n,p,q,k] * x[n, p+r-pad_h, q+s-pad_w, c]
 //
@@ -16,23 +16,23 @@
 // of 32, and WP wavefronts per block that take 32 pixels each of a 32*WP-pixel chunk.  The WP wavefronts
 // of a block add their accumulators up through LDS at the end (a fixed tree, so the result is the same
 // bits every run), and only one of them stores: the partial sums that leave the CU, and the number of
-// splits of the pixel range across work-groups, shrink WP times.  LDS is double buffered: one barrier
-// per chunk.
+// splits of the pixel range across work-groups, shrink WP times.
 //
-// Vector-ALU instructions.  In-kernel cycle counters showed that on this chip the fp32 MFMA does not run
-// beside vector-ALU work of the same SIMD, whichever wavefront issues it: a wavefront's address
-// arithmetic took three times as long while the SIMD's other wavefront was in its MFMA phase, and a
-// chunk took the MFMA time plus the vector-ALU time of both wavefronts whatever the order of their
-// phases.  So every vector instruction in the chunk loop costs matrix time, and the loop is written to
-// have almost none:
-//  * the padded row width WPC and the filter width SW are template parameters, so the LDS address of
-//    tap (r,s) is one per-pixel base (read from a table of byte offsets) plus an immediate offset;
-//  * what the loaders need to know about a chunk (which pixel a panel row shows, where a pixel's panel row
-//    is) comes from two small LDS tables instead of divisions;
-//  * global loads are buffer loads: a thread's offsets into the dz chunk are constants, the chunk's
-//    base goes into the buffer descriptor (scalar arithmetic), and whatever must read as zero (rows past
-//    the end of the tensor, filters or channels past the end of a ragged tile, padding pixels) gets an
-//    offset beyond the descriptor's range, which the hardware turns into zeros without touching memory.
+// What the chunk loop avoids, and why (in-kernel cycle counters on this chip):
+//  * Vector-ALU instructions.  The fp32 MFMA does not run beside vector-ALU work of the same SIMD,
+//    whichever wavefront issues it: a wavefront's address arithmetic took three times as long while the
+//    SIMD's other wavefront was in its MFMA phase, and a chunk took the MFMA time plus the vector-ALU time
+//    of both wavefronts whatever the order of their phases.  So the padded row width WPC and the filter
+//    width SW are template parameters (the LDS address of tap (r,s) is a per-pixel base, read from a table
+//    of byte offsets, plus an immediate), the loaders take what they need to know about a chunk from two
+//    small LDS tables instead of divisions, and whatever must read as zero (rows past the end of the
+//    tensor, filters or channels past the end of a ragged tile, padding pixels) gets a buffer offset beyond
+//    its descriptor's range, which the hardware turns into zeros without touching memory.
+//  * Staging through registers.  Writing a chunk into LDS from registers took a tenth of the kernel: all
+//    wavefronts wait for their loads, push 60 KB through ds_write and wait again before the next fragment
+//    read.  Here buffer loads write LDS directly (16 bytes per lane, 1 KB per wavefront instruction, lane l
+//    at base + 16 l): the next chunk lands in the other stage while this one is multiplied, with one
+//    barrier per chunk.  Rows are unpadded (a fragment read runs along a row).
 #pragma once
 #include <type_traits>
 
@@ -40,38 +40,54 @@
 
 namespace owt {
 
-typedef unsigned int owt_u32x4 __attribute__((ext_vector_type(4)));
+typedef int owt_i32x4 __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t rsrc, unsigned voffset_bytes)
+// Raw buffer descriptor (base, byte count) in scalar registers.
+__device__ __forceinline__ owt_i32x4 make_rsrc(const void *base, unsigned bytes)
 {
-    const owt_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset_bytes, 0, 0);
-    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+    const unsigned long long a = (unsigned long long)base;
+    owt_i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from the buffer straight into LDS: lane l's piece lands at LDS byte address lds_base + 16 l;
+// a lane whose offset is outside the descriptor's range writes zeros.  (m0 carries the LDS base; the s_nop is
+// the wait state the hardware wants between a scalar write of m0 and the load that reads it.)
+__device__ __forceinline__ void buffer_load16_to_lds(owt_i32x4 rsrc, unsigned voffset_bytes, unsigned lds_base)
+{
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);       // wave-uniform by construction
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+                 : : "v"(voffset_bytes), "s"(rsrc), "s"(m0v) : "memory", "m0");
 }
 
 // SW > 0: all R x SW taps in one work-group (TAPS == R*SW), padded rows WPC pixels wide.
 // SW == 0: one filter row of TAPS taps per work-group (any row width).
-template <int WK, int WP, int TAPS, int SW, int WPC, int PRF, bool MASKED>
+// PROWS: panel rows per stage, a multiple of 64.
+template <int WK, int WP, int TAPS, int SW, int WPC, int PROWS>
 __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmParams p)
 {
-    constexpr int NT = 64 * WK * WP, KT = 32 * WK, CT = 32, BP = 32 * WP;
-    constexpr int PA = KT + 4, PB = CT + 4;
-    constexpr int KQ = KT / 4, ARPP = NT / KQ, ANP = BP / ARPP;          // dz loader
-    // x panel loader: a thread fetches the LPT 16-byte pieces bq, bq + TPR, ... of one panel row
-    constexpr int CQ = CT / 4, LPT = 4, TPR = CQ / LPT, BRPP = NT / TPR, BNP = (PRF + BRPP - 1) / BRPP;
-    static_assert(CQ % LPT == 0 && NT % TPR == 0, "panel rows must split evenly over the threads");
-    static_assert(BP % ARPP == 0 && NT % KQ == 0, "dz chunk must split evenly over the threads");
+    constexpr int NW = WK * WP, NT = 64 * NW, KT = 32 * WK, CT = 32, BP = 32 * WP;
+    constexpr int ALPR = KT / 4, ARPI = 64 / ALPR, AI = BP / ARPI / NW;     // dz: lanes per row, rows per instruction, instructions per wavefront
+    constexpr int BI = PROWS / 8 / NW;                                      // panel: 8 rows of 128 bytes per instruction
+    static_assert(BP % (ARPI * NW) == 0 && PROWS % (8 * NW) == 0, "a stage must split into whole 1 KB instructions per wavefront");
     static_assert((WP & (WP - 1)) == 0 && WP >= 2, "the pixel parts are added up in a binary tree");
     static_assert(SW == 0 || TAPS % SW == 0, "taps = filter rows x filter width");
-    constexpr int STAGE = BP * PA + PRF * PB + BP;                       // floats: dz rows, panel, row table
+    static_assert(BP * KT == 16 * NT, "the bias-gradient sums take 16 rows per thread");
+    constexpr int STAGE = BP * KT + PROWS * CT + BP;                     // floats: dz rows, panel, row table
     // taps per round of the final tree: the writers' accumulators of one round must fit the two stages
     constexpr int RED_SLOTS = WK * WP / 2, TG_MAX = (2 * STAGE) / (RED_SLOTS * 16 * 64);
     constexpr int TG = TG_MAX < TAPS ? TG_MAX : TAPS;
     static_assert(TG >= 1, "LDS too small for the reduction tree");
-    static_assert(ARPP * KT <= 2 * STAGE, "LDS too small for the bias-gradient sums");
     constexpr unsigned OOB = 0x80000000u;                                // a byte offset no descriptor here reaches
     constexpr int TABMAX = 1024;                                         // entries of each of the two loader tables
 
-    __shared__ __attribute__((aligned(16))) float lds[2 * STAGE];
+    __shared__ __attribute__((aligned(1024))) float lds[2 * STAGE];
+    __shared__ unsigned xoff_tab[TABMAX];
+    __shared__ int prow_tab[TABMAX];
 
     const Geom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -92,51 +108,37 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
     const int r0 = p.groups > 1 ? grp : 0, rows_g = p.groups > 1 ? 1 : g.R;
     const int tap_first = p.groups > 1 ? grp * g.S : 0;
 
-    // padded linear index of the window's top-left corner of pixel pix
-    auto ppad = [&](int pix) {
-        const int n = g.dPQ.div(pix), pq = pix - n * g.P * g.Q;
-        const int pp = g.dQ.div(pq), q = pq - pp * g.Q;
-        return (n * p.Hp + pp) * Wp + q;
-    };
-
-    // ---- loaders.  Two tables in LDS, filled once, replace the per-chunk divisions (integer multiplies run at
-    // a quarter of the vector rate, and vector instructions cost matrix time here):
+    // ---- loader tables, filled once:
     //   xoff_tab[pos], pos < Hp*Wp: byte offset inside an image of the pixel that padded position pos shows, or OOB;
-    //   prow_tab[pq],  pq < P*Q:    PB*4 times the padded position of output pixel pq's window corner.
-    // A chunk touches at most two images (host-checked: BP <= P*Q and PRF <= Hp*Wp), so a thread only has to
+    //   prow_tab[pq],  pq < P*Q:    128 (bytes per panel row) times the padded position of output pixel pq's window corner.
+    // A chunk touches at most two images (host-checked: BP <= P*Q and PROWS <= Hp*Wp), so a lane only has to
     // decide which of the two it is in: compare, conditional subtract, table read.
-    __shared__ unsigned xoff_tab[TABMAX];
-    __shared__ int prow_tab[TABMAX];
     const int IP = p.Hp * Wp, PQ = g.P * g.Q;
-    for (int pos = threadIdx.x; pos < IP; pos += NT) {
+    for (int pos = tid; pos < IP; pos += NT) {
         const int hp = p.dWp.div(pos), wp = pos - hp * Wp, h = hp - g.ph, w = wp - g.pw;
         xoff_tab[pos] = ((unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W) ? (unsigned)((h * g.W + w) * g.C) * 4u : OOB;
     }
-    for (int pq = threadIdx.x; pq < PQ; pq += NT) {
+    for (int pq = tid; pq < PQ; pq += NT) {
         const int pp = g.dQ.div(pq), q = pq - pp * g.Q;
-        prow_tab[pq] = (pp * Wp + q) * (PB * 4);
+        prow_tab[pq] = (pp * Wp + q) * (CT * 4);
     }
-    __syncthreads();
-    // Per-thread constants: byte offsets of the thread's ANP pieces inside a dz chunk, the panel pieces it owns,
-    // and which of its pieces exist at all (ragged last filter / channel tile).
-    const int akq = tid % KQ, arow0 = tid / KQ;
-    const int bq = tid % TPR, brow0 = tid / TPR;
-    unsigned avoff[ANP];
+
+    // ---- per-lane constants of the loaders.  Instruction i of this wavefront is number q = wave + NW*i of the
+    // stage: dz instruction q covers rows ARPI*q .. of the chunk, panel instruction q rows 8q .. 8q+7.
+    unsigned avoff[AI];                   // byte offset of this lane's piece inside the chunk's dz rows, or OOB
 #pragma unroll
-    for (int i = 0; i < ANP; i++)
-        avoff[i] = k0 + akq * 4 < g.K ? (unsigned)(((arow0 + i * ARPP) * g.K + k0 + akq * 4) * 4) : OOB;
-    unsigned bpiece[LPT];                 // byte offset of piece j inside the pixel, or OOB
-#pragma unroll
-    for (int j = 0; j < LPT; j++) bpiece[j] = c0 + (bq + j * TPR) * 4 < g.C ? (unsigned)((c0 + (bq + j * TPR) * 4) * 4) : OOB;
-    const bool c_full = c0 + CT <= g.C;   // uniform: every piece of the channel tile exists
-    const __amdgpu_buffer_rsrc_t xrsrc =
-        __builtin_amdgcn_make_buffer_rsrc((void *)p.b, 0, (int)((unsigned)g.N * g.H * g.W * g.C * 4u), 0x00020000);
+    for (int i = 0; i < AI; i++) {
+        const int row = (wave + NW * i) * ARPI + lane / ALPR, k = k0 + (lane % ALPR) * 4;
+        avoff[i] = k < g.K ? (unsigned)((row * g.K + k) * 4) : OOB;
+    }
+    const unsigned bcoff = c0 + (lane & 7) * 4 < g.C ? (unsigned)((c0 + (lane & 7) * 4) * 4) : OOB;   // this lane's piece inside a pixel
+    const int brow_l = wave * 8 + (lane >> 3);                       // its panel row in instruction 0; instruction i: + 8*NW*i
+    const unsigned lds_base = (unsigned)(size_t)(__attribute__((address_space(3))) float *)lds;
+    const owt_i32x4 xrsrc = make_rsrc(p.b, (unsigned)g.N * g.H * g.W * g.C * 4u);
     const unsigned img_bytes = (unsigned)(g.H * g.W * g.C) * 4u;
 
-    float4 areg[ANP], breg[BNP][LPT];
-    int tab_next = 0;
-
-    auto load_chunk = [&](int ch) {
+    // All loads of chunk ch, into stage `stage`.  Nothing is waited for here.
+    auto issue_chunk = [&](int ch, int stage) {
         // wavefront-uniform bookkeeping of the chunk (scalar unit)
         const int pix0 = ch * BP, lim = min(pix0 + BP, npix);
         const int n0 = g.dPQ.div(pix0), pq0 = pix0 - n0 * PQ;
@@ -144,71 +146,30 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
         const int pos0 = (pp0 + r0) * Wp + q0;                    // first panel row's padded position in image n0
         const int nl = g.dPQ.div(lim - 1), pql = lim - 1 - nl * PQ;
         const int ppl = g.dQ.div(pql), ql = pql - ppl * g.Q;
-        const int nrows = (nl - n0) * IP + (ppl + r0 + rows_g - 1) * Wp + ql + g.S - pos0;   // <= PRF (host-checked)
+        const int nrows = (nl - n0) * IP + (ppl + r0 + rows_g - 1) * Wp + ql + g.S - pos0;   // <= PROWS (host-checked)
         const unsigned img0 = (unsigned)n0 * img_bytes, img1 = n0 + 1 < g.N ? img0 + img_bytes : OOB;
+        const unsigned sbase = lds_base + (unsigned)stage * (STAGE * 4);
         // dz rows pix0 .. pix0 + BP - 1: the descriptor starts at the chunk and ends with the tensor
-        const unsigned left = (unsigned)(npix - pix0) * g.K * 4u;
-        const __amdgpu_buffer_rsrc_t arsrc =
-            __builtin_amdgcn_make_buffer_rsrc((void *)((const float *)p.a + (size_t)pix0 * g.K), 0, (int)left, 0x00020000);
+        const owt_i32x4 arsrc = make_rsrc((const float *)p.a + (size_t)pix0 * g.K, (unsigned)(npix - pix0) * g.K * 4u);
 #pragma unroll
-        for (int i = 0; i < ANP; i++) areg[i] = buffer_load4(arsrc, avoff[i]);
-        if constexpr (MASKED) {           // dz = dy * [y > 0]: applied on arrival (this variant waits for its loads here)
-            const __amdgpu_buffer_rsrc_t mrsrc =
-                __builtin_amdgcn_make_buffer_rsrc((void *)((const float *)p.mask + (size_t)pix0 * g.K), 0, (int)left, 0x00020000);
+        for (int i = 0; i < AI; i++) buffer_load16_to_lds(arsrc, avoff[i], sbase + (unsigned)(wave + NW * i) * 1024u);
+        // panel row -> padded position in image n0 or n0 + 1 -> the pixel it shows, or none (padding, past the rows
+        // this chunk needs, past the last image)
+        unsigned bvoff[BI];
 #pragma unroll
-            for (int i = 0; i < ANP; i++) {
-                const float4 y = buffer_load4(mrsrc, avoff[i]);
-                areg[i].x = y.x > 0.f ? areg[i].x : 0.f; areg[i].y = y.y > 0.f ? areg[i].y : 0.f;
-                areg[i].z = y.z > 0.f ? areg[i].z : 0.f; areg[i].w = y.w > 0.f ? areg[i].w : 0.f;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < BNP; i++) {
-            // panel row -> padded position in image n0 or n0 + 1 -> the pixel it shows, or none (padding, past the
-            // rows this chunk needs, past the last image)
-            const int row = brow0 + i * BRPP, pos = pos0 + row;
-            const bool second = pos >= IP;
+        for (int i = 0; i < BI; i++) {
+            const int row = brow_l + 8 * NW * i, pos = pos0 + row;
             const unsigned t = xoff_tab[min((unsigned)pos, (unsigned)(pos - IP))];
-            const unsigned pixoff = row < nrows ? t + (second ? img1 : img0) : OOB;      // OOB + anything stays >= OOB
-            if (c_full) {
-                const unsigned v0 = pixoff + (unsigned)((c0 + bq * 4) * 4);
-#pragma unroll
-                for (int j = 0; j < LPT; j++) breg[i][j] = buffer_load4(xrsrc, v0 + j * TPR * 16);
-            } else {
-#pragma unroll
-                for (int j = 0; j < LPT; j++) breg[i][j] = buffer_load4(xrsrc, (pixoff | bpiece[j]) >= OOB ? OOB : pixoff + bpiece[j]);
-            }
+            const unsigned pixoff = row < nrows ? t + (pos >= IP ? img1 : img0) : OOB;        // OOB + an image offset stays >= OOB
+            bvoff[i] = __builtin_elementwise_add_sat(pixoff, bcoff);
         }
+#pragma unroll
+        for (int i = 0; i < BI; i++) buffer_load16_to_lds(xrsrc, bvoff[i], sbase + (unsigned)(BP * KT * 4) + (unsigned)(wave + NW * i) * 1024u);
         if (tid < BP) {       // byte offset of each pixel's panel row relative to the chunk's first
             const int pq = pq0 + tid;
-            const bool second = pq >= PQ;
-            const int v = prow_tab[min((unsigned)pq, (unsigned)(pq - PQ))] + ((second ? IP : 0) + r0 * Wp - pos0) * (PB * 4);
-            tab_next = pix0 + tid < lim ? v : 0;
+            const int v = prow_tab[min((unsigned)pq, (unsigned)(pq - PQ))] + ((pq >= PQ ? IP : 0) + r0 * Wp - pos0) * (CT * 4);
+            ((int *)(lds + stage * STAGE + BP * KT + PROWS * CT))[tid] = pix0 + tid < lim ? v : 0;
         }
-    };
-    float4 dbacc = make_float4(0.f, 0.f, 0.f, 0.f);
-    const bool do_db = ct == 0 && grp == 0 && p.dbias != nullptr;
-    auto store_chunk = [&](int stage) {
-        float *dzs = lds + stage * STAGE, *panel = dzs + BP * PA;
-        int *tab = (int *)(panel + PRF * PB);
-#pragma unroll
-        for (int i = 0; i < ANP; i++)
-            *(float4 *)(dzs + (arow0 + i * ARPP) * PA + akq * 4) = areg[i];
-        if (do_db) {
-#pragma unroll
-            for (int i = 0; i < ANP; i++) {
-                dbacc.x += areg[i].x; dbacc.y += areg[i].y; dbacc.z += areg[i].z; dbacc.w += areg[i].w;
-            }
-        }
-#pragma unroll
-        for (int i = 0; i < BNP; i++) {
-            const int row = brow0 + i * BRPP;
-            if (BNP * BRPP <= PRF || row < PRF) {
-#pragma unroll
-                for (int j = 0; j < LPT; j++) *(float4 *)(panel + row * PB + (bq + j * TPR) * 4) = breg[i][j];
-            }
-        }
-        if (tid < BP) tab[tid] = tab_next;
     };
 
     float16v acc[TAPS];
@@ -216,24 +177,26 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
     for (int t = 0; t < TAPS; t++)
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[t][r] = 0.f;
+    float dbacc = 0.f;
+    const bool do_db = ct == 0 && grp == 0 && p.dbias != nullptr;
 
     // Sixteen pixels (eight MFMA steps of two) of this wavefront's 32, from one LDS stage.  Two fragment sets
     // ping-pong so the LDS reads of the next pixel pair are issued before the MFMAs of the current one; a
     // pair's panel row is looked up one fetch ahead of its use.  Every address below is a per-lane base that
     // is set up once per call plus an immediate offset.
     auto compute16 = [&](int stage, int pfirst) {
-        const float *dzs = lds + stage * STAGE, *panel = dzs + BP * PA;
-        const int *tab = (const int *)(panel + PRF * PB) + pfirst + lh;           // this lane's pixels: tab[2 * pair]
-        const float *abase = dzs + (pfirst + lh) * PA + wk0 + li;                 // a of pair: abase[2 * pair * PA]
+        const float *dzs = lds + stage * STAGE, *panel = dzs + BP * KT;
+        const int *tab = (const int *)(panel + PROWS * CT) + pfirst + lh;         // this lane's pixels: tab[2 * pair]
+        const float *abase = dzs + (pfirst + lh) * KT + wk0 + li;                 // a of pair: abase[2 * pair * KT]
         const char *pbase_l = (const char *)(panel + li);
         auto fetch = [&](auto pair_c, int &prow, float &a, float (&bb)[TAPS]) {
             constexpr int pair = decltype(pair_c)::value;
             const float *pb = (const float *)(pbase_l + prow);
-            a = abase[2 * pair * PA];
+            a = abase[2 * pair * KT];
 #pragma unroll
             for (int t = 0; t < TAPS; t++) {
                 constexpr int sw = SW > 0 ? SW : 1;
-                bb[t] = pb[(SW > 0 ? (t / sw) * WPC + t % sw : t) * PB];
+                bb[t] = pb[(SW > 0 ? (t / sw) * WPC + t % sw : t) * CT];
             }
             prow = tab[2 * pair + 4 <= 14 ? 2 * pair + 4 : 14];
         };
@@ -257,24 +220,30 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
 #undef OWT_DF2_STEP
     };
 
-    if (ch_beg < ch_end) { load_chunk(ch_beg); store_chunk(0); }
-    __syncthreads();
+    __syncthreads();                                    // the loader tables are complete
+    if (ch_beg < ch_end) issue_chunk(ch_beg, 0);
 
     int cur = 0;
     for (int ch = ch_beg; ch < ch_end; ch++) {
-        const bool more = ch + 1 < ch_end;
-        if (more) load_chunk(ch + 1);
+        // this lane's pieces of chunk ch have landed and its row-table entry is written; after the barrier that
+        // holds for the whole work-group, and every wavefront is done reading the other stage (chunk ch - 1)
+        __builtin_amdgcn_s_waitcnt(0x0070);             // vmcnt(0) lgkmcnt(0), expcnt untouched
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");                  // no LDS read of this stage moves above the barrier
+        if (ch + 1 < ch_end) issue_chunk(ch + 1, cur ^ 1);
         compute16(cur, pbase);
-        // the other stage was last read before the barrier that ended the previous chunk
-        if (more) store_chunk(cur ^ 1);
         compute16(cur, pbase + 16);
-        __syncthreads();
+        if (do_db) {          // bias gradient: column sums of the chunk's dz rows, 16 rows per thread
+            const float *col = lds + cur * STAGE + (tid / KT) * 16 * KT + tid % KT;
+#pragma unroll
+            for (int j = 0; j < 16; j++) dbacc += col[j * KT];
+        }
         cur ^= 1;
     }
+    __syncthreads();                                    // every wavefront is done with the stages
 
     // ---- the WP pixel parts of a filter block add up through LDS: in every round the upper half of the
-    // remaining parts writes TG taps at a time, the lower half adds.  (All stage memory is free: every
-    // wavefront has passed the loop's last barrier.)
+    // remaining parts writes TG taps at a time, the lower half adds.
 #pragma unroll
     for (int stride = WP / 2; stride >= 1; stride >>= 1) {
 #pragma unroll
@@ -324,11 +293,11 @@ __global__ void __launch_bounds__(64 * WK * WP, 1) dfilter2_kernel(const GemmPar
 
     if (do_db) {   // uniform over the work-group; the tree above ended with a barrier
         float *red = lds;
-        *(float4 *)(red + arow0 * KT + akq * 4) = dbacc;
+        red[tid] = dbacc;                               // [row group][filter]
         __syncthreads();
         if (tid < KT && k0 + tid < g.K) {
             float s = 0.f;
-            for (int j = 0; j < ARPP; j++) s += red[j * KT + tid];
+            for (int j = 0; j < NT / KT; j++) s += red[j * KT + tid];
             const int k = k0 + tid;
             if (parts) p.dbias_partial[(size_t)split * p.M + k] = s;
             else p.dbias[k] = p.alpha * s + (p.beta != 0.f ? p.beta * p.dbias[k] : 0.f);

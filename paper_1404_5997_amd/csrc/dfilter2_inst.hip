@@ -9,8 +9,8 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     constexpr DFilter2Variant v = kDFilter2Variants[V];
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    if (p.mask) hipLaunchKernelGGL((dfilter2_kernel<v.WK, v.WP, v.tmax, v.SW, v.WPC, v.prf, true>), grid, dim3(64 * v.WK * v.WP), 0, s, p);
-    else hipLaunchKernelGGL((dfilter2_kernel<v.WK, v.WP, v.tmax, v.SW, v.WPC, v.prf, false>), grid, dim3(64 * v.WK * v.WP), 0, s, p);
+    if (p.mask) return hipErrorInvalidValue;       // the planner sends masked calls to dfilter.hpp
+    hipLaunchKernelGGL((dfilter2_kernel<v.WK, v.WP, v.tmax, v.SW, v.WPC, v.prows>), grid, dim3(64 * v.WK * v.WP), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
     return e;

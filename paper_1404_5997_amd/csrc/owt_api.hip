@@ -44,7 +44,7 @@ static inline size_t pad256(size_t n) { return (n + 255) & ~(size_t)255; }
 bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh, int sw, int ph, int pw)
 {
     g.N = N; g.C = C; g.H = H; g.W = W; g.K = K; g.R = R; g.S = S;
-    g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw; g.bf16 = 0;
+    g.sh = sh; g.sw = sw; g.ph = ph; g.pw = pw; g.bf16 = 0; g.masked = 0;
     g.P = (H + 2 * ph - R) / sh + 1;
     g.Q = (W + 2 * pw - S) / sw + 1;
     if (H + 2 * ph - R < 0 || W + 2 * pw - S < 0) return false;
@@ -160,7 +160,7 @@ static bool dfilter_fits(const Geom &g, int variant, int &taps, int &groups)
 static bool dfilter2_fits(const Geom &g, int variant, int &taps, int &groups)
 {
     const DFilter2Variant &v = kDFilter2Variants[variant];
-    if (g.bf16 || g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W || g.C % 4 || g.K % 4) return false;
+    if (g.bf16 || g.masked || g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W || g.C % 4 || g.K % 4) return false;
     const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q, last = 32 * v.WP - 1;
     if (v.SW > 0) {
         if (g.S != v.SW || g.R * g.S != v.tmax || Wp != v.WPC) return false;
@@ -171,11 +171,11 @@ static bool dfilter2_fits(const Geom &g, int variant, int &taps, int &groups)
     }
     // buffer descriptors hold byte counts in 32 bits, and bit 31 of an offset marks "reads as zero"
     if ((long)g.N * g.H * g.W * g.C * 4 >= 0x7fffffffL || (long)g.N * PQ * g.K * 4 >= 0x7fffffffL) return false;
-    // the loaders' two LDS tables have 1024 entries, and a chunk (pixels and panel rows) may touch two images at most
-    if (Hp * Wp > 1024 || PQ > 1024 || 32 * v.WP > PQ || v.prf > Hp * Wp) return false;
+    // the loaders' two LDS tables have 1024 entries, and a chunk may touch two images at most
+    if (Hp * Wp > 1024 || PQ > 1024 || 32 * v.WP > PQ) return false;
     const long span = last + (last / g.Q + 1) * (Wp - g.Q) + (last / PQ + 1) * (Hp - g.P) * Wp;
     const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
-    return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
+    return rows <= v.prows && (long)g.N * Hp * Wp < 0x7fffffffL;
 }
 
 // The same for the bf16-MFMA variant (64-pixel chunks, 16-byte pieces: C and K multiples of 8).
@@ -604,7 +604,7 @@ static std::mutex g_tuned_mutex;
 
 static PlanKey plan_key(const Geom &g, int pass, owt_dtype dt)
 {
-    return PlanKey{g.N, g.C, g.H, g.W, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, pass, (int)dt, 0, 0};
+    return PlanKey{g.N, g.C, g.H, g.W, g.K, g.R, g.S, g.sh, g.sw, g.ph, g.pw, pass, (int)dt, g.masked, 0};
 }
 
 static bool variants_forced()
@@ -796,6 +796,7 @@ static owt_status check_conv(const owt_conv_desc *d, Geom &g)
     if (!fill_geom(g, d->N, d->C, d->H, d->W, d->K, d->R, d->S, d->stride_h, d->stride_w, d->pad_h, d->pad_w))
         return fail(OWT_EINVAL, "filter larger than the padded input: no output");
     g.bf16 = d->dtype == OWT_BF16;
+    g.masked = (d->flags & OWT_RELU) ? 1 : 0;       // backward calls then mask dy by y > 0 themselves
     const long xe = (long)d->N * d->H * d->W * d->C, ye = (long)d->N * g.P * g.Q * d->K,
                we = (long)d->K * d->R * d->S * d->C;
     if (xe > kMaxElems || ye > kMaxElems || we > kMaxElems)

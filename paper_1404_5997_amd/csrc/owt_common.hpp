@@ -29,6 +29,7 @@ struct FastDiv {
 struct Geom {
     int N, C, H, W, K, R, S, sh, sw, ph, pw, P, Q;
     int bf16;                 // storage type of the tensors is bf16 (host-side planning only)
+    int masked;               // the backward call applies a ReLU mask to dy itself (host-side planning only)
     FastDiv dC, dS, dK, dQ, dPQ, dW, dHW, dsh, dsw;
 };
 

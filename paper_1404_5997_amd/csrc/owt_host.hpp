@@ -57,15 +57,15 @@ constexpr DFilterVariant kDFilterVariants[kNumDFilterVariants] = {
 hipError_t owt_launch_dfilter_f32(int variant, const GemmParams &, hipStream_t);
 hipError_t owt_launch_dfilter_bf16(int variant, const GemmParams &, hipStream_t);
 
-// Filter-gradient kernel with the pixel reduction split inside the work-group (dfilter2_inst.hip; fp32
-// storage): WK filter blocks of 32 x WP pixel parts of 32 pixels, 32 channels, tmax taps per work-group,
-// prf panel rows; one work-group of 8 wavefronts per CU.  SW > 0: all taps of an R x SW filter on
-// padded rows exactly WPC pixels wide (both compile-time constants of the kernel); SW == 0: one filter row
-// of tmax taps per work-group, any row width.
-struct DFilter2Variant { int WK, WP, tmax, SW, WPC, prf; };
+// Filter-gradient kernel with the pixel reduction split inside the work-group and operands streamed straight
+// into LDS (dfilter2_inst.hip; fp32 storage, dz not masked by the call): WK filter blocks of 32 x WP pixel
+// parts of 32 pixels, 32 channels, tmax taps per work-group, prows panel rows per LDS stage; one work-group of
+// 8 wavefronts per CU.  SW > 0: all taps of an R x SW filter on padded rows exactly WPC pixels wide (both
+// compile-time constants of the kernel); SW == 0: one filter row of tmax taps per work-group, any row width.
+struct DFilter2Variant { int WK, WP, tmax, SW, WPC, prows; };
 constexpr int kNumDFilter2Variants = 3;
 constexpr DFilter2Variant kDFilter2Variants[kNumDFilter2Variants] = {
-    {2, 4, 9, 3, 15, 224}, {4, 2, 9, 3, 15, 144}, {2, 4, 5, 0, 0, 288}};
+    {2, 4, 9, 3, 15, 256}, {4, 2, 9, 3, 15, 192}, {2, 4, 5, 0, 0, 320}};
 constexpr int kDFilter2FirstTile = 10;      // owt_test_force_variant: tile numbers 10.. name these variants
 hipError_t owt_launch_dfilter2_f32(int variant, const GemmParams &, hipStream_t);
 

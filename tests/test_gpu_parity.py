@@ -172,22 +172,28 @@ def test_filter_gradient_with_chunks_cut_per_image(split):
 
 @pytest.mark.parametrize("variant,split", [(0, 1), (0, 2), (0, 3), (1, 1), (1, 4), (1, 6), (2, 1), (2, 3), (2, 5)])
 def test_filter_gradient_with_the_pixel_split_inside_the_work_group(variant, split):
-    # fp32 filter gradient whose work-groups split a chunk of pixels over several wavefronts per filter block and
-    # add the parts up through LDS (variants 0, 1: all nine taps of a 3x3 layer on maps 13 pixels wide, chunks of
-    # 128 / 64 pixels; variant 2: one row of five taps per work-group), forced, alone and split over work-groups:
-    # ragged filter and channel tiles, a last chunk with 41 or 1 valid pixels, masked dz, alpha / beta, no bias
+    # fp32 filter gradient whose work-groups split a chunk of pixels over several wavefronts per filter block, add
+    # the parts up through LDS and stream their operands straight into LDS (variants 0, 1: all nine taps of a 3x3
+    # layer on maps 13 pixels wide, chunks of 128 / 64 pixels; variant 2: one row of five taps per work-group),
+    # forced, alone and split over work-groups: ragged filter and channel tiles, a last chunk with 41 or 1 valid
+    # pixels, chunks that straddle two images, alpha / beta, with and without bias gradient.  The kernel takes dz
+    # as it is; a call that masks dy itself (OWT_RELU) must be served by another kernel.
     m = owt()
     with force(10 + variant, split, m.OWT_FORCE_ONLY_DIRECT):
-        shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 12, 21, 12, 3, 5, (1, 2)), dict(relu=False, alpha=0.5, beta=-0.25)),
+        shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 12, 21, 12, 3, 5, (1, 2)), dict(alpha=0.5, beta=-0.25)),
                   ((1, 36, 13, 21, 64, 5, 5, 2), dict(bias=False))] if variant == 2 else \
                  [((4, 40, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
-                  ((1, 8, 13, 13, 8, 3, 3, 1), dict(relu=False, alpha=1.0 / 3, beta=1.0)), ((7, 32, 13, 13, 64, 3, 3, 1), {}),
+                  ((1, 8, 13, 13, 8, 3, 3, 1), dict(alpha=1.0 / 3, beta=1.0)), ((7, 32, 13, 13, 64, 3, 3, 1), {}),
                   ((3, 36, 17, 13, 68, 3, 3, 1), dict(alpha=0.5, beta=-0.25))]           # H != W, ragged in K and C
         for (N, C, H, W, K, R, S, pad), kw in shapes:
-            d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
+            d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_F32, m.OWT_BIAS)
             assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("dfilter2"), \
                 m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER)
-            layer_parity(N, C, H, W, K, R, S, 1, pad, seed=600 + 10 * variant + split, **kw)
+            layer_parity(N, C, H, W, K, R, S, 1, pad, relu=False, seed=600 + 10 * variant + split, **kw)
+        N, C, H, W, K, R, S, pad = shapes[0][0]
+        d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
+        assert not m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("dfilter2")
+        layer_parity(N, C, H, W, K, R, S, 1, pad, relu=True, seed=650 + variant)
 
 
 @pytest.mark.parametrize("tile,split", [(0, 1), (1, 1), (4, 1), (0, 2), (1, 3), (4, 2), (7, 1), (7, 2), (7, 3), (8, 1), (8, 2)])
