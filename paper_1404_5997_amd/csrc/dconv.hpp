@@ -18,6 +18,8 @@
 // Ho <= Hi and Wo <= Wi, so the pixels of a row tile form one contiguous range;
 // taps that fall outside the image read a row of zeros instead.
 #pragma once
+#include <type_traits>
+
 #include "igemm.hpp"
 
 namespace owt {
@@ -84,7 +86,46 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) dconv_kernel(const GemmPara
     const int bquad = tid % BQUADS, bline0 = tid / BQUADS;
     float4 preg[PNP], breg[BNP];
 
+    // fp32 storage with whole chunks (Cred a multiple of BK; tensors under 2 GiB): loads go through buffer
+    // descriptors.  What must read as zero gets an offset outside the descriptor (panel rows past the tile's
+    // range or outside the tensor, filters past the last one), so a load costs one vector add for its address
+    // and nothing else: on this chip vector-ALU work and fp32 MFMAs of a SIMD do not overlap.
+    constexpr unsigned OOB = 0x80000000u;
+    const bool fast = std::is_same<T, float>::value && Cred % BK == 0 &&
+                      (size_t)npix_in * Cred * 4 < OOB && (size_t)p.g.K * RS * p.g.C * 4 < OOB;
+    const __amdgpu_buffer_rsrc_t in_rsrc = owt_make_rsrc(p.a, (unsigned)npix_in * Cred * 4u);
+    const __amdgpu_buffer_rsrc_t mask_rsrc = owt_make_rsrc(p.mask ? p.mask : p.a, (unsigned)npix_in * Cred * 4u);
+    const __amdgpu_buffer_rsrc_t w_rsrc = owt_make_rsrc(p.b, (unsigned)p.g.K * RS * p.g.C * 4u);
+    unsigned pvoff[PNP], bvoff[BNP];          // per-thread constants: byte offset inside the panel / the filter slice, or OOB
+#pragma unroll
+    for (int i = 0; i < PNP; i++) {
+        const int row = prow0 + i * PRPP;
+        pvoff[i] = row < nrows ? (unsigned)((row * Cred + pquad * 4) * 4) : OOB;
+    }
+#pragma unroll
+    for (int i = 0; i < BNP; i++) {
+        const int line = bline0 + i * BRPP;
+        if (BKM) bvoff[i] = n0 + line < p.Ncols ? (unsigned)((((n0 + line) * RS) * Cred + bquad * 4) * 4) : OOB;
+        else bvoff[i] = n0 + bquad * 4 < p.Ncols ? (unsigned)(((line * RS) * p.Ncols + n0 + bquad * 4) * 4) : OOB;
+    }
+
     auto load_panel = [&](int ch) {
+        if (fast) {
+            // rows of pixels before the tensor's first wrap to offsets near 2^32: outside the descriptor as well
+            const unsigned base = (unsigned)((ps * Cred + ch * BK) * 4);
+#pragma unroll
+            for (int i = 0; i < PNP; i++) {
+                const unsigned vo = pvoff[i] >= OOB ? OOB : pvoff[i] + base;
+                float4 v = buffer_load4(in_rsrc, vo);
+                if (BWD && mask) {
+                    const float4 y = buffer_load4(mask_rsrc, vo);
+                    v.x = y.x > 0.f ? v.x : 0.f; v.y = y.y > 0.f ? v.y : 0.f;
+                    v.z = y.z > 0.f ? v.z : 0.f; v.w = y.w > 0.f ? v.w : 0.f;
+                }
+                preg[i] = v;
+            }
+            return;
+        }
         const int c = ch * BK + pquad * 4;
 #pragma unroll
         for (int i = 0; i < PNP; i++) {
@@ -110,6 +151,13 @@ __global__ void __launch_bounds__(64 * WM * WN, OCC) dconv_kernel(const GemmPara
         }
     };
     auto load_b = [&](int ch, int tap) {
+        if (fast) {
+            const unsigned base = BKM ? (unsigned)((tap * Cred + ch * BK) * 4)
+                                      : (unsigned)(((ch * BK * RS + (RS - 1 - tap)) * p.Ncols) * 4);
+#pragma unroll
+            for (int i = 0; i < BNP; i++) breg[i] = buffer_load4(w_rsrc, bvoff[i] >= OOB ? OOB : bvoff[i] + base);
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < BNP; i++) {
             const int line = bline0 + i * BRPP;

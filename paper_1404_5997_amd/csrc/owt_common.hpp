@@ -88,6 +88,19 @@ __device__ __forceinline__ float4 load4(const bf16_t *p, int off)
     return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
                        __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
 }
+// 16 bytes through a raw buffer descriptor: a byte offset outside [0, bytes) reads as zeros without touching
+// memory, so bounds need no branch, no exec masking and no zeroing of the destination.
+typedef unsigned int owt_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t owt_make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)bytes, 0x00020000);
+}
+__device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t rsrc, unsigned voffset_bytes)
+{
+    const owt_u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (int)voffset_bytes, 0, 0);
+    return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
+}
+
 __device__ __forceinline__ float load1(const float *p, int off) { return p[off]; }
 __device__ __forceinline__ float load1(const bf16_t *p, int off) { return bf16_to_f32(p[off].bits); }
 
