@@ -260,7 +260,7 @@ static bool sconv_geom(const Geom &g, SConvGeom &sg)
     const int zr = (orows - 1) * g.sh + (sg.KSLOTS - 1) / sg.SLOTS + 1;
     sg.ZROWS = zr > sg.ROWS + 1 ? zr : sg.ROWS + 1;
     const size_t lds = ((size_t)2 * 64 * (kSConvBK + 4) + (size_t)sg.ZROWS * sg.PITCH) * 4;
-    return sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 && sg.SLOTS >= 8 &&
+    return sg.MPIX <= 256 && lds <= 150 * 1024 && sg.ROWS < 256 && sg.SLOTS >= 8 && sg.KSLOTS <= 2048 &&
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
 }
 
@@ -1169,16 +1169,38 @@ static owt_status check_fc(const owt_fc_desc *d, Geom &g, int &o_local)
     return OWT_OK;
 }
 
+// Workspace every candidate of the shard's passes fits in, remembered per geometry: the backward call checks
+// it on every launch, and listing the candidates costs microseconds on a path whose kernels take ten.
+static std::map<PlanKey, size_t> g_fc_ws;
+
+static size_t fc_workspace(const Geom &g, owt_dtype dt, int pass)
+{
+    const PlanKey key = plan_key(g, 4 + (pass == OWT_PASS_FWD ? 0 : 1), dt);
+    if (!variants_forced()) {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        auto it = g_fc_ws.find(key);
+        if (it != g_fc_ws.end()) return it->second;
+    }
+    size_t need;
+    if (pass == OWT_PASS_FWD) need = max_workspace(g, OWT_PASS_FWD, conv_dims(g, OWT_PASS_FWD), false);
+    else {      // the backward call runs the data pass, then the filter pass, on one scratch area
+        const size_t a = max_workspace(g, OWT_PASS_BWD_DATA, conv_dims(g, OWT_PASS_BWD_DATA), false);
+        const size_t b = max_workspace(g, OWT_PASS_BWD_FILTER, conv_dims(g, OWT_PASS_BWD_FILTER), true);
+        need = a > b ? a : b;
+    }
+    if (!variants_forced()) {
+        std::lock_guard<std::mutex> lk(g_tuned_mutex);
+        g_fc_ws[key] = need;
+    }
+    return need;
+}
+
 size_t owt_fc_workspace_bytes(const owt_fc_desc *d, int pass)
 {
     Geom g; int ol;
     if (pass < 0 || pass > 2) { fail(OWT_EINVAL, "pass must be 0, 1 or 2"); return (size_t)-1; }
     if (check_fc(d, g, ol) != OWT_OK) return (size_t)-1;
-    if (pass == OWT_PASS_FWD) return max_workspace(g, OWT_PASS_FWD, conv_dims(g, OWT_PASS_FWD), false);
-    // the backward call runs the data pass, then the filter pass, on one scratch area
-    const size_t a = max_workspace(g, OWT_PASS_BWD_DATA, conv_dims(g, OWT_PASS_BWD_DATA), false);
-    const size_t b = max_workspace(g, OWT_PASS_BWD_FILTER, conv_dims(g, OWT_PASS_BWD_FILTER), true);
-    return a > b ? a : b;
+    return fc_workspace(g, d->dtype, pass);
 }
 
 owt_status owt_fc_shard_fwd(const owt_fc_desc *d, const void *x, const void *w, const float *bias,
@@ -1205,7 +1227,7 @@ owt_status owt_fc_shard_bwd(const owt_fc_desc *d, const void *x, const void *w, 
     if (dx_partial_or_null) OWT_TRY(check_ptr(dx_partial_or_null, "dx_partial"));
     if (dbias_or_null) OWT_TRY(check_ptr(dbias_or_null, "dbias"));
     if (d->flags & OWT_RELU) OWT_TRY(check_ptr(y_or_null, "y (needed for the ReLU mask)"));
-    const size_t need = owt_fc_workspace_bytes(d, OWT_PASS_BWD_DATA);
+    const size_t need = fc_workspace(g, d->dtype, OWT_PASS_BWD_DATA);
     if (ws_bytes < need) return fail(OWT_EWORKSPACE, "workspace too small: need %zu bytes, got %zu", need, ws_bytes);
     if (need && (!ws || !aligned16(ws))) return fail(OWT_EINVAL, "ws is NULL or misaligned");
     const void *mask = (d->flags & OWT_RELU) ? y_or_null : nullptr;

@@ -14,6 +14,8 @@
 // pixels x 64 filters.  Work-groups loop over (image, band) units with the next
 // band prefetched into registers.
 #pragma once
+#include <type_traits>
+
 #include "igemm.hpp"
 
 namespace owt {
@@ -44,6 +46,10 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     extern __shared__ __attribute__((aligned(16))) float slds[];
     float *Bs = slds;                                           // 2 x KB x WP
     float *panel = slds + 2 * KB * WP;                          // ZROWS x PITCH; rows >= ROWS stay zero
+    // qoff[Q]: panel offset (floats) of reduction quad Q = (filter row Q / qpr, quad Q % qpr of that row).  Looked
+    // up instead of being tracked with compares, selects and a multiply per group of eight MFMAs: vector-ALU
+    // instructions take MFMA time on this chip, LDS reads next to none.
+    __shared__ int qoff[512];
 
     const Geom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -54,6 +60,7 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
     const int qpr = sg.SLOTS / 4;                               // quads per filter row
 
     for (int i = tid; i < sg.ZROWS * sg.PITCH; i += NT) panel[i] = 0.f;
+    for (int i = tid; i < sg.KSTEPS * BQ; i += NT) qoff[i] = (i / qpr) * sg.PITCH + (i % qpr) * 4;
     __syncthreads();
 
     const T *xsrc = (const T *)p.a;
@@ -73,9 +80,25 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
         const int row = i / row_f4, f4 = i - row * row_f4;
         prf[it] = i < panel_f4 ? (row | (f4 << 8)) : -1;
     }
+    // fp32 storage: loads go through buffer descriptors (an offset outside the descriptor reads as zeros), so a
+    // piece that does not exist costs no branch, no exec masking and no zeroing
+    constexpr unsigned OOB = 0x80000000u;
+    const bool fast = std::is_same<T, float>::value && (size_t)g.N * g.H * g.W * g.C * 4 < OOB;
+    const __amdgpu_buffer_rsrc_t x_rsrc = owt_make_rsrc(p.a, (unsigned)g.N * g.H * g.W * g.C * 4u);
+    const __amdgpu_buffer_rsrc_t w2_rsrc = owt_make_rsrc(w2, (unsigned)g.K * sg.KSLOTS * 4u);
     auto load_band = [&](int u) {
         const int n = u / sg.units_per_image, p0 = g.dQ.div((u - n * sg.units_per_image) * BAND);
         const int h0 = p0 * g.sh - g.ph;                        // first input row of the band's first output row
+        if (fast) {
+            const int img = n * g.H * row_f4 * 16;                // byte offset of the image
+#pragma unroll
+            for (int it = 0; it < PNP; it++) {
+                const int row = prf[it] & 255, f4 = prf[it] >> 8, h = h0 + row;
+                const bool ok = prf[it] >= 0 && (unsigned)h < (unsigned)g.H;
+                preg[it] = buffer_load4(x_rsrc, ok ? (unsigned)(img + (h * row_f4 + f4) * 16) : OOB);
+            }
+            return;
+        }
 #pragma unroll
         for (int it = 0; it < PNP; it++) {
             const int row = prf[it] & 255, f4 = prf[it] >> 8, h = h0 + row;
@@ -89,13 +112,15 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
         for (int it = 0; it < PNP; it++)
             if (prf[it] >= 0) *(float4 *)(panel + (prf[it] & 255) * sg.PITCH + img_off + (prf[it] >> 8) * 4) = preg[it];
     };
+    unsigned bvoff[BPASS];             // byte offset of this thread's filter-slice pieces at step 0, or OOB
+#pragma unroll
+    for (int it = 0; it < BPASS; it++) {
+        const int line = bl0 + it * BLPP, k = k0 + line;
+        bvoff[it] = (line < KB && k < g.K) ? (unsigned)((k * sg.KSLOTS + bq * 4) * 4) : OOB;
+    }
     auto load_b = [&](int step) {
 #pragma unroll
-        for (int it = 0; it < BPASS; it++) {
-            const int line = bl0 + it * BLPP, k = k0 + line;
-            breg[it] = (line < KB && k < g.K) ? *(const float4 *)(w2 + (size_t)k * sg.KSLOTS + step * BK + bq * 4)
-                                              : make_float4(0.f, 0.f, 0.f, 0.f);
-        }
+        for (int it = 0; it < BPASS; it++) breg[it] = buffer_load4(w2_rsrc, __builtin_elementwise_add_sat(bvoff[it], (unsigned)(step * BK * 4)));
     };
     auto store_b = [&](float *buf) {
 #pragma unroll
@@ -126,20 +151,27 @@ __global__ void __launch_bounds__(kSConvNT, 2) sconv_fwd_kernel(const GemmParams
         for (int i = 0; i < 2; i++)
 #pragma unroll
             for (int r = 0; r < 16; r++) acc[i][r] = 0.f;
-        // quad index step*BQ + 2*cc + lh of this lane, as (filter row qr, quad qj of that row): advanced by
-        // two quads per group instead of dividing every time (BQ is even, a row has at least two quads)
-        int qr = 0, qj = lh;
-        if (qj >= qpr) { qj -= qpr; qr++; }
+        // this lane's quad of group cc in step `step` is Q = step*BQ + 2*cc + lh; its panel offsets come from the table,
+        // read one step ahead, and are masked to zero for a lane without a pixel (its base is the row of zeros)
+        const int omask = mvalid ? -1 : 0;
+        const int *qt = qoff + lh;
+        int onext[BQ / 2];
+#pragma unroll
+        for (int cc = 0; cc < BQ / 2; cc++) onext[cc] = qt[2 * cc];
         for (int step = 0; step < sg.KSTEPS; step++) {
             const bool last = step + 1 == sg.KSTEPS;
             if (!last || more_u) load_b(last ? 0 : step + 1);
             if (step == 0 && more_u) load_band(u + 1);          // held in registers until the band is done
             const float *Bc = Bs + cur * KB * WP;
+            int ocur[BQ / 2];
+#pragma unroll
+            for (int cc = 0; cc < BQ / 2; cc++) ocur[cc] = onext[cc];
+            const int *qn = qt + (last ? 0 : (step + 1) * BQ);
+#pragma unroll
+            for (int cc = 0; cc < BQ / 2; cc++) onext[cc] = qn[2 * cc];
 #pragma unroll
             for (int cc = 0; cc < BQ / 2; cc++) {
-                const float4 a = *(const float4 *)(panel + abase + (mvalid ? qr * sg.PITCH + qj * 4 : 0));
-                qj += 2;
-                if (qj >= qpr) { qj -= qpr; qr++; }
+                const float4 a = *(const float4 *)(panel + abase + (ocur[cc] & omask));
                 const float4 b0 = *(const float4 *)(Bc + li * WP + (2 * cc + lh) * 4);
                 const float4 b1 = *(const float4 *)(Bc + (32 + li) * WP + (2 * cc + lh) * 4);
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, b0.x, acc[0], 0, 0, 0);
