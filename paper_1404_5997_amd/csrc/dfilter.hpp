@@ -23,7 +23,12 @@
 namespace owt {
 
 // OCC = work-groups per CU the register budget is cut for.
-template <class T, int WK, int WC, int TAPS, int PRF, int OCC>
+// FAST (fp32 storage, chunks cut per image, one filter row per work-group; the launcher checks what it needs):
+// the chunk loader and the fragment fetch are written for few vector-ALU instructions, which take MFMA time
+// on this chip.  Loads go through buffer descriptors (what must read as zero gets an offset outside the
+// descriptor), the position of a panel row in the image and of a pixel's window come from two LDS tables
+// instead of divisions, and the taps of a filter row are immediate offsets from one address.
+template <class T, int WK, int WC, int TAPS, int PRF, int OCC, bool FAST = false>
 __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmParams p)
 {
     constexpr int NT = 64 * WK * WC, KT = 32 * WK, CT = 32 * WC, BP = 32;
@@ -38,6 +43,10 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
     __shared__ __attribute__((aligned(16))) float dzs[BP * PA];
     __shared__ __attribute__((aligned(16))) float panel[PRF * PB];
     __shared__ int prow_tab[BP];
+    constexpr int XTAB = FAST ? 1152 : 1, QTAB = FAST ? 1024 : 1;
+    __shared__ unsigned xoff_tab[XTAB];      // padded position in an image -> byte offset of the pixel it shows, or OOB
+    __shared__ int win_tab[QTAB];            // output pixel of an image -> padded position of its window's corner
+    constexpr unsigned OOB = 0x80000000u;
 
     const Geom &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -83,7 +92,52 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
             lim = min(pix0 + BP, npix);
         }
     };
+    // ---- FAST loader state: per-thread constant offsets, descriptors
+    unsigned avoff[ANP], bcoff[LPT];
+    __amdgpu_buffer_rsrc_t xrsrc = owt_make_rsrc(p.b, 0);
+    if constexpr (FAST) {
+        const int IPt = p.Hp * Wp, PQt = g.P * g.Q;
+        for (int pos = tid; pos < XTAB; pos += NT) {
+            const int hp = p.dWp.div(pos), wp = pos - hp * Wp, h = hp - g.ph, w = wp - g.pw;
+            xoff_tab[pos] = (pos < IPt && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W)
+                                ? (unsigned)((h * g.W + w) * g.C) * 4u : OOB;
+        }
+        for (int pq = tid; pq < PQt; pq += NT) {
+            const int pp = g.dQ.div(pq), q = pq - pp * g.Q;
+            win_tab[pq] = pp * Wp + q;
+        }
+#pragma unroll
+        for (int i = 0; i < ANP; i++)
+            avoff[i] = k0 + akq * 4 < g.K ? (unsigned)(((arow0 + i * ARPP) * g.K + k0 + akq * 4) * 4) : OOB;
+#pragma unroll
+        for (int j = 0; j < LPT; j++)
+            bcoff[j] = c0 + (bq + j * TPR) * 4 < g.C ? (unsigned)((c0 + (bq + j * TPR) * 4) * 4) : OOB;
+        xrsrc = owt_make_rsrc(p.b, (unsigned)g.N * g.H * g.W * g.C * 4u);
+        __syncthreads();
+    }
+    auto load_chunk_fast = [&](int ch) {
+        // chunk ch = pixels [pq0, pql] of image n (uniform, scalar unit)
+        const int n = p.dCpi.div(ch), pq0 = (ch - n * p.cpi) * BP, PQt = g.P * g.Q, pql = min(pq0 + BP, PQt) - 1;
+        const int pp0 = g.dQ.div(pq0), ppl = g.dQ.div(pql);
+        const int pos0 = (pp0 + r0) * Wp + (pq0 - pp0 * g.Q);                               // first panel row: padded position in the image
+        const int nrows = (ppl + r0 + rows_g - 1) * Wp + (pql - ppl * g.Q) + g.S - pos0;     // <= PRF (host-checked)
+        const __amdgpu_buffer_rsrc_t arsrc =
+            owt_make_rsrc(dzsrc + (size_t)(n * PQt + pq0) * g.K, (unsigned)(pql + 1 - pq0) * g.K * 4u);   // ends with the chunk
+        const unsigned img = (unsigned)n * (unsigned)(g.H * g.W * g.C) * 4u;
+#pragma unroll
+        for (int i = 0; i < ANP; i++) areg[i] = buffer_load4(arsrc, avoff[i]);
+#pragma unroll
+        for (int i = 0; i < BNP; i++) {
+            const int row = brow0 + i * BRPP;
+            const unsigned t = xoff_tab[min(pos0 + row, XTAB - 1)];
+            const unsigned pixoff = row < nrows ? t + img : OOB;               // OOB + an image offset stays >= OOB
+#pragma unroll
+            for (int j = 0; j < LPT; j++) breg[i][j] = buffer_load4(xrsrc, __builtin_elementwise_add_sat(pixoff, bcoff[j]));
+        }
+        if (tid < BP) tab_next = pq0 + tid <= pql ? win_tab[pq0 + tid] + r0 * Wp - pos0 : 0;
+    };
     auto load_chunk = [&](int ch) {
+        if constexpr (FAST) { load_chunk_fast(ch); return; }
         int pix0, lim;
         chunk_range(ch, pix0, lim);
         const int ps = ppad(pix0) + r0 * Wp;
@@ -174,8 +228,14 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
             const int pix = 2 * pair + lh;
             const int base = prow * PB;
             a = dzs[pix * PA + wk0 + li];
+            if constexpr (FAST) {            // one filter row: tap t is t pixels to the right of tap 0
+                const float *pb = panel + base + wc0 + li;
 #pragma unroll
-            for (int t = 0; t < TAPS; t++) b[t] = panel[base + toff[t]];
+                for (int t = 0; t < TAPS; t++) b[t] = pb[t * PB];
+            } else {
+#pragma unroll
+                for (int t = 0; t < TAPS; t++) b[t] = panel[base + toff[t]];
+            }
             prow = prow_tab[min(pix + 4, BP - 1)];
         };
         auto mma = [&](float a, const float (&b)[TAPS]) {

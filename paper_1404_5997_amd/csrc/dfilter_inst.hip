@@ -22,7 +22,15 @@ static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     constexpr DFilterVariant v = kDFilterVariants[V];
     const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
-    hipLaunchKernelGGL((dfilter_kernel<TT, v.WK, v.WC, v.tmax, v.prf, v.occ>), grid, dim3(64 * v.WK * v.WC), 0, s, p);
+    // the low-vector-ALU form of the loader and fetch: fp32 storage, chunks cut per image, one filter row per
+    // work-group, dz not masked by the call, tables and byte offsets within their ranges
+    const long IP = (long)p.Hp * p.Wp, PQ = (long)p.g.P * p.g.Q;
+    const bool fast = !OWT_INST_BF16 && v.aligned && p.cpi > 0 && p.groups > 1 && !p.mask && IP + v.prf <= 1152 && PQ <= 1024 &&
+                      (long)p.g.N * p.g.H * p.g.W * p.g.C * 4 < 0x7fffffffL && (long)p.g.N * PQ * p.g.K * 4 < 0x7fffffffL;
+    if (v.aligned && !OWT_INST_BF16 && fast)
+        hipLaunchKernelGGL((dfilter_kernel<TT, v.WK, v.WC, v.tmax, v.prf, v.occ, v.aligned && !OWT_INST_BF16>), grid, dim3(64 * v.WK * v.WC), 0, s, p);
+    else
+        hipLaunchKernelGGL((dfilter_kernel<TT, v.WK, v.WC, v.tmax, v.prf, v.occ>), grid, dim3(64 * v.WK * v.WC), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);
     return e;

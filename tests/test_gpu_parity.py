@@ -162,7 +162,9 @@ def test_filter_gradient_with_chunks_cut_per_image(split):
     # pixel chunks never straddle two images (small panel, three work-groups per CU), forced, fp32 and bf16 storage
     m = owt()
     with force(3, split):
-        for (N, C, K), kw in [((3, 64, 72), {}), ((1, 8, 200), dict(relu=False, alpha=0.5, beta=-0.25)), ((5, 36, 64), dict(bias=False))]:
+        # (calls that take dz as it is, relu=False, run the form of the kernel with table-driven loaders and buffer loads)
+        for (N, C, K), kw in [((3, 64, 72), {}), ((1, 8, 200), dict(relu=False, alpha=0.5, beta=-0.25)), ((5, 36, 64), dict(bias=False)),
+                              ((3, 64, 72), dict(relu=False)), ((5, 36, 68), dict(relu=False, bias=False)), ((2, 64, 192), dict(relu=False, alpha=0.5, beta=1.0))]:
             d = m.conv_desc(N, C, 27, 27, K, 5, 5, 1, 2, m.OWT_F32, m.OWT_BIAS | m.OWT_RELU)
             assert "chunks-per-image" in m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER), m.owt_conv_plan_describe(d, 2)
             layer_parity(N, C, 27, 27, K, 5, 5, 1, 2, seed=800 + split, **kw)
