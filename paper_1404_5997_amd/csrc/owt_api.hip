@@ -58,7 +58,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -264,6 +264,15 @@ static bool sconv_geom(const Geom &g, SConvGeom &sg)
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSConvNT * kSConvPNP;
 }
 
+// The first-layer forward kernel that keeps 32 filters' whole bank in LDS beside the band: fp32 storage, LDS
+// capacity, and 32-bit byte offsets into x and y for its buffer descriptors.
+static bool sconv2_fits(const Geom &g, const SConvGeom &sg)
+{
+    const size_t lds = ((size_t)kSConv2KB * (sg.KSLOTS + 4) + (size_t)sg.ZROWS * sg.PITCH) * 4;
+    const size_t xb = (size_t)g.N * g.H * g.W * g.C * 4, yb = (size_t)g.N * g.P * g.Q * g.K * 4;
+    return lds <= 157 * 1024 && xb < 0x7fffffffull && yb < 0x7fffffffull && sg.KSTEPS * (kSConvBK / 4) <= 512;
+}
+
 struct Launch {
     int kind, tile, splits, steps, steps_per_split, tiles_m, tiles_n, pr, taps, groups, ctiles;
     size_t partial_bytes, dbias_bytes;
@@ -372,7 +381,27 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     SConvGeom scg;
-    if (pass == OWT_PASS_FWD && !no_direct && sconv_geom(g, scg)) {
+    // test hook: tile 20 = only the filter-streaming first-layer forward kernel, 21 = only the filters-in-LDS one
+    const bool sconv_ok = pass == OWT_PASS_FWD && !no_direct && sconv_geom(g, scg);
+    if (sconv_ok && force_tile != 20 && !g.bf16 && sconv2_fits(g, scg)) {
+        const long ktiles = cdiv(g.K, kSConv2KB);
+        for (long target : {256L, 512L}) {
+            long wgs = target / ktiles > 0 ? target / ktiles : 1;
+            if (force_split > 0) wgs = force_split;
+            if (wgs > scg.units) wgs = scg.units;
+            const long per = cdiv(scg.units, wgs), n = cdiv(scg.units, per);
+            Launch l; memset(&l, 0, sizeof(l));
+            l.kind = KIND_SCONV2; l.splits = 1; l.steps = scg.units; l.steps_per_split = (int)per;
+            l.tiles_m = (int)ktiles; l.tiles_n = (int)n;
+            l.partial_bytes = pad256((size_t)g.K * scg.KSLOTS * 4);          // the re-laid-out filters
+            l.cost = model_cost(ktiles * n, 8, 1, 256.0 * kSConv2KB * scg.KSLOTS * per, 1.2, 1, dm.M, dm.Ncols);
+            bool dup = false;
+            for (const Launch &o : out) dup |= o.kind == l.kind && o.tiles_n == l.tiles_n;
+            if (!dup) out.push_back(l);
+            if (force_split > 0) break;
+        }
+    }
+    if (sconv_ok && force_tile != 21) {
         const long ktiles = cdiv(g.K, 64);
         for (long target : {256L, 512L}) {
             long wgs = target / ktiles > 0 ? target / ktiles : 1;
@@ -678,6 +707,12 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         sg.units_per_wg = l.steps_per_split;
         p.splits = 1; p.partial = nullptr;
         e = owt_launch_sconv16(p, sg, l.tiles_m, l.tiles_n, ws, s);
+    } else if (l.kind == KIND_SCONV2) {
+        SConvGeom sg;
+        sconv_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        p.splits = 1; p.partial = nullptr;
+        e = owt_launch_sconv2_f32(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s);
     } else if (l.kind == KIND_SCONV) {
         SConvGeom sg;
         sconv_geom(g, sg);
@@ -739,6 +774,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     if (l.kind == KIND_SCONV16)
         return snprintf(buf, n, "sconv16 %s %s rows%d grid%dx%d threads%ld", pn[pass], ds, kSConv16TP, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConv16NT);
+    if (l.kind == KIND_SCONV2)
+        return snprintf(buf, n, "sconv2 %s %s band%d filters%d grid%dx%d threads%ld", pn[pass], ds, kSConvBand, kSConv2KB, l.tiles_m,
+                        l.tiles_n, (long)l.tiles_m * ((l.tiles_n + 7) / 8) * 8 * kSConvNT);
     if (l.kind == KIND_SCONV)
         return snprintf(buf, n, "sconv %s %s band%d grid%dx%d threads%ld", pn[pass], ds, kSConvBand, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConvNT);
@@ -985,7 +1023,7 @@ int owt_selftest_host(void)
             if (c.empty()) { fail(OWT_EINVAL, "no candidate for shape N=%d C=%d pass %d", sh[0], sh[1], pass); return 3; }
             const size_t bound = max_workspace(g, pass, dm, pass == OWT_PASS_BWD_FILTER);
             for (const Launch &l : c) {
-                const long parts = (l.kind == KIND_SCONV || l.kind == KIND_SCONV16) ? l.tiles_n : l.splits;   // who shares the steps
+                const long parts = (l.kind == KIND_SCONV || l.kind == KIND_SCONV2 || l.kind == KIND_SCONV16) ? l.tiles_n : l.splits;   // who shares the steps
                 if (l.splits < 1 || parts * l.steps_per_split < l.steps ||
                     (parts - 1) * l.steps_per_split >= l.steps || l.ws_bytes() > bound ||
                     ((l.kind == KIND_DIRECT || l.kind == KIND_DIRECT16) && (l.pr > 624 || direct_panel_rows(g, pass, dm, kTiles[l.tile].BM) > l.pr))) {

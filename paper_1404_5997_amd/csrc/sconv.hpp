@@ -24,6 +24,7 @@ struct SConvGeom {
     int SEG, LPAD, SLOTS, PITCH, ROWS, ZROWS, KSLOTS, KSTEPS, units_per_image, units, units_per_wg, MPIX;
 };
 constexpr int kSConvNT = 512, kSConvBand = 256, kSConvBK = 40, kSConvPNP = 11;
+constexpr int kSConv2KB = 32;      // filters per work-group of the filters-in-LDS form (sconv2.hpp)
 
 // w2[k][t] = w[k][r][jj - LPAD] for t = r*SLOTS + jj inside the filter, else 0 (fp32, K x KSLOTS)
 template <class T>

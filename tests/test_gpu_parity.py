@@ -263,6 +263,12 @@ def test_strided_small_channel_kernels(shape, split):
             layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", seed=220 + split)
     with force(-1, split, m.OWT_FORCE_ONLY_DIRECT | m.OWT_FORCE_NO_BF16_MFMA):   # ... and the fp32-MFMA kernels on bf16 storage
         layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, seed=230 + split)
+    # the two fp32 forward kernels, each forced: filters streamed in slices / the whole bank of 32 filters in LDS
+    for tile, name in ((20, "sconv "), (21, "sconv2 ")):
+        with force(tile, split, m.OWT_FORCE_ONLY_DIRECT):
+            assert m.owt_conv_plan_describe(d, m.OWT_PASS_FWD).startswith(name), m.owt_conv_plan_describe(d, 0)
+            layer_parity(N, C, H, W, K, R, S, stride, pad, seed=240 + split)
+            layer_parity(N, C, H, W, K, R, S, stride, pad, relu=False, bias=False, seed=250 + split)
 
 
 def test_autotune_keeps_results_and_is_remembered():
