@@ -40,30 +40,6 @@
 
 namespace owt {
 
-typedef int owt_i32x4 __attribute__((ext_vector_type(4)));
-
-// Raw buffer descriptor (base, byte count) in scalar registers.
-__device__ __forceinline__ owt_i32x4 make_rsrc(const void *base, unsigned bytes)
-{
-    const unsigned long long a = (unsigned long long)base;
-    owt_i32x4 r;
-    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
-    r.y = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));
-    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
-    r.w = 0x00020000;
-    return r;
-}
-
-// 16 bytes per lane from the buffer straight into LDS: lane l's piece lands at LDS byte address lds_base + 16 l;
-// a lane whose offset is outside the descriptor's range writes zeros.  (m0 carries the LDS base; the s_nop is
-// the wait state the hardware wants between a scalar write of m0 and the load that reads it.)
-__device__ __forceinline__ void buffer_load16_to_lds(owt_i32x4 rsrc, unsigned voffset_bytes, unsigned lds_base)
-{
-    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);       // wave-uniform by construction
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
-                 : : "v"(voffset_bytes), "s"(rsrc), "s"(m0v) : "memory", "m0");
-}
-
 // SW > 0: all R x SW taps in one work-group (TAPS == R*SW), padded rows WPC pixels wide.
 // SW == 0: one filter row of TAPS taps per work-group (any row width).
 // PROWS: panel rows per stage, a multiple of 64.

@@ -58,7 +58,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11, KIND_SFILTER2 = 12 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -273,6 +273,16 @@ static bool sconv2_fits(const Geom &g, const SConvGeom &sg)
     return lds <= 157 * 1024 && xb < 0x7fffffffull && yb < 0x7fffffffull && sg.KSTEPS * (kSConvBK / 4) <= 512;
 }
 
+// The first-layer filter-gradient kernel whose units stream straight into two LDS stages: fp32 storage, dz taken
+// as it is, both stages within LDS, the loaders' instruction counts, 32-bit byte offsets inside one image.
+static bool sfilter2_fits(const Geom &g, const SFilterGeom &sg)
+{
+    const long pan_inst = ((long)sg.ROWS * (sg.PITCH / 4) + 63) / 64, dz_inst = ((long)sg.DZP * 17 + 63) / 64;
+    const size_t lds = (size_t)2 * (pan_inst + dz_inst) * 1024 + (size_t)sg.DZP * 4;
+    return !g.bf16 && !g.masked && pan_inst <= 8 * kSFilter2PNI && dz_inst <= 8 * kSFilter2DNI && lds <= 158 * 1024 &&
+           (size_t)g.H * g.W * g.C * 4 < 0x40000000ull && (size_t)g.P * g.Q * g.K * 4 < 0x40000000ull;
+}
+
 struct Launch {
     int kind, tile, splits, steps, steps_per_split, tiles_m, tiles_n, pr, taps, groups, ctiles;
     size_t partial_bytes, dbias_bytes;
@@ -439,8 +449,12 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (force_split > 0) break;
         }
     }
+    // test hook: tile 22 = only the register-staged first-layer filter-gradient kernel, 23 = only the one that streams
+    // its units straight into LDS
     SFilterGeom sfg;
-    if (pass == OWT_PASS_BWD_FILTER && !no_direct && (g.sh > 1 || g.sw > 1) && sfilter_geom(g, sfg)) {
+    const bool sfilter_ok = pass == OWT_PASS_BWD_FILTER && !no_direct && (g.sh > 1 || g.sw > 1) && sfilter_geom(g, sfg);
+    for (int form = 0; form < 2 && sfilter_ok; form++) {
+        if (form == 0 ? force_tile == 23 : (force_tile == 22 || !sfilter2_fits(g, sfg))) continue;
         const long ktiles = cdiv(g.K, 64);
         for (long target : {256L, 512L, 1024L}) {
             long wgs = target / ktiles > 0 ? target / ktiles : 1;
@@ -448,13 +462,13 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (wgs > sfg.units) wgs = sfg.units;
             const long per = cdiv(sfg.units, wgs), splits = cdiv(sfg.units, per);
             Launch l; memset(&l, 0, sizeof(l));
-            l.kind = KIND_SFILTER; l.tile = 0; l.splits = (int)splits; l.steps = sfg.units; l.steps_per_split = (int)per;
+            l.kind = form ? KIND_SFILTER2 : KIND_SFILTER; l.tile = 0; l.splits = (int)splits; l.steps = sfg.units; l.steps_per_split = (int)per;
             l.tiles_m = (int)ktiles; l.tiles_n = 1;
             if (splits > 1) {
                 l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                 l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
             }
-            l.cost = model_cost(ktiles * splits, 8, 2, 64.0 * sfg.NB * 32 * sfg.DZP * per, 1.0, splits, dm.M, dm.Ncols);
+            l.cost = model_cost(ktiles * splits, 8, form ? 1 : 2, 64.0 * sfg.NB * 32 * sfg.DZP * per, form ? 1.15 : 1.0, splits, dm.M, dm.Ncols);
             bool dup = false;
             for (const Launch &o : out) dup |= o.kind == l.kind && o.splits == l.splits;
             if (!dup) out.push_back(l);
@@ -725,6 +739,11 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         sfilter16_geom(g, sg);
         sg.units_per_wg = l.steps_per_split;
         e = owt_launch_sfilter16(p, sg, l.tiles_m, s);
+    } else if (l.kind == KIND_SFILTER2) {
+        SFilterGeom sg;
+        sfilter_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        e = owt_launch_sfilter2_f32(p, sg, l.tiles_m, s);
     } else if (l.kind == KIND_SFILTER) {
         SFilterGeom sg;
         sfilter_geom(g, sg);
@@ -783,6 +802,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     if (l.kind == KIND_SFILTER16)
         return snprintf(buf, n, "sfilter16 %s %s rows%d splitk%d grid%dx%d threads%ld", pn[pass], ds, kSFilter16TP, l.splits,
                         l.tiles_m, l.splits, (long)l.tiles_m * l.splits * kSFilter16NT);
+    if (l.kind == KIND_SFILTER2)
+        return snprintf(buf, n, "sfilter2 %s %s rows2 splitk%d grid%dx%d threads%ld", pn[pass], ds, l.splits, l.tiles_m,
+                        l.splits, (long)l.tiles_m * l.splits * kSFilterNT);
     if (l.kind == KIND_SFILTER)
         return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d threads%ld", pn[pass], ds, l.splits, l.tiles_m,
                         l.splits, (long)l.tiles_m * l.splits * kSFilterNT);

@@ -101,6 +101,30 @@ __device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t rsrc, unsi
     return make_float4(__uint_as_float(v.x), __uint_as_float(v.y), __uint_as_float(v.z), __uint_as_float(v.w));
 }
 
+typedef int owt_i32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor (base, byte count) in scalar registers.
+__device__ __forceinline__ owt_i32x4 make_rsrc(const void *base, unsigned bytes)
+{
+    const unsigned long long a = (unsigned long long)base;
+    owt_i32x4 r;
+    r.x = __builtin_amdgcn_readfirstlane((int)(unsigned)a);
+    r.y = __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu));
+    r.z = __builtin_amdgcn_readfirstlane((int)bytes);
+    r.w = 0x00020000;
+    return r;
+}
+
+// 16 bytes per lane from the buffer straight into LDS: lane l's piece lands at LDS byte address lds_base + 16 l;
+// a lane whose offset is outside the descriptor's range writes zeros.  (m0 carries the LDS base; the s_nop is
+// the wait state the hardware wants between a scalar write of m0 and the load that reads it.)
+__device__ __forceinline__ void buffer_load16_to_lds(owt_i32x4 rsrc, unsigned voffset_bytes, unsigned lds_base)
+{
+    const unsigned m0v = __builtin_amdgcn_readfirstlane(lds_base);       // wave-uniform by construction
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tbuffer_load_dwordx4 %0, %1, 0 offen lds"
+                 : : "v"(voffset_bytes), "s"(rsrc), "s"(m0v) : "memory", "m0");
+}
+
 __device__ __forceinline__ float load1(const float *p, int off) { return p[off]; }
 __device__ __forceinline__ float load1(const bf16_t *p, int off) { return bf16_to_f32(p[off].bits); }
 

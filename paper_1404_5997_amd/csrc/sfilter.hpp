@@ -25,6 +25,9 @@ struct SFilterGeom {
 // float4 staged per thread and unit: input rows (kSFilterPNP) and dz rows (kSFilterDNP)
 constexpr int kSFilterNT = 512, kSFilterACCS = 4, kSFilterPNP = 5, kSFilterDNP = 4;      // ACCS: the larger of the two instantiations
 
+// direct-to-LDS instructions per wavefront and unit of the form that streams its units into LDS (sfilter2.hpp)
+constexpr int kSFilter2PNI = 6, kSFilter2DNI = 4;
+
 template <class T, int NT, int ACCS, int PNP, int DNP>
 __global__ void __launch_bounds__(NT, 2) sfilter_kernel(const GemmParams p, const SFilterGeom sg)
 {

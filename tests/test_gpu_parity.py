@@ -269,6 +269,17 @@ def test_strided_small_channel_kernels(shape, split):
             assert m.owt_conv_plan_describe(d, m.OWT_PASS_FWD).startswith(name), m.owt_conv_plan_describe(d, 0)
             layer_parity(N, C, H, W, K, R, S, stride, pad, seed=240 + split)
             layer_parity(N, C, H, W, K, R, S, stride, pad, relu=False, bias=False, seed=250 + split)
+    # the two fp32 filter-gradient kernels, each forced: units staged through registers / streamed straight into LDS
+    # (the second takes dz as it is: a call that passes y for the ReLU' mask is served by the first)
+    dn = m.conv_desc(N, C, H, W, K, R, S, stride, pad, m.OWT_F32, m.OWT_BIAS)
+    for tile, name in ((22, "sfilter "), (23, "sfilter2 ")):
+        with force(tile, split, m.OWT_FORCE_ONLY_DIRECT):
+            assert m.owt_conv_plan_describe(dn, m.OWT_PASS_BWD_FILTER).startswith(name), m.owt_conv_plan_describe(dn, 2)
+            layer_parity(N, C, H, W, K, R, S, stride, pad, relu=False, seed=260 + split)
+            layer_parity(N, C, H, W, K, R, S, stride, pad, relu=False, bias=False, alpha=0.5, beta=-0.25, seed=270 + split)
+            if tile == 23:
+                assert not m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("sfilter2")
+                layer_parity(N, C, H, W, K, R, S, stride, pad, seed=280 + split)
 
 
 def test_autotune_keeps_results_and_is_remembered():
