@@ -33,6 +33,7 @@ def _units():
     units.append(("fcgemm.o", "fcgemm_inst.hip", []))
     units.append(("dfilter2.o", "dfilter2_inst.hip", []))
     units.append(("dfilter16.o", "dfilter_bf16_inst.hip", []))
+    units.append(("dfilter16b.o", "dfilter16b_inst.hip", []))
     units.append(("sconv16.o", "sconv_bf16_inst.hip", []))
     units.append(("sfilter16.o", "sfilter_bf16_inst.hip", []))
     for bf in (0, 1):

@@ -58,7 +58,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11, KIND_SFILTER2 = 12 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11, KIND_SFILTER2 = 12, KIND_DFILTER16B = 13 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -190,6 +190,27 @@ static bool dfilter16_fits(const Geom &g, int variant, int &taps, int &groups)
     const long span = last + (last / g.Q + 1) * (Wp - g.Q) + (last / PQ + 1) * (Hp - g.P) * Wp;
     const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
     return rows <= v.prf && (long)g.N * Hp * Wp < 0x7fffffffL;
+}
+
+// The bf16 filter-gradient kernel whose operands stream straight into LDS: as above, plus dz taken as it is, loader
+// tables of 1024 entries, chunks that touch at most two images, and 32-bit byte offsets into x.
+static bool dfilter16b_fits(const Geom &g, int variant, int &taps, int &groups)
+{
+    const DFilter16bVariant &v = kDFilter16bVariants[variant];
+    if (!g.bf16 || g.masked || g.sh != 1 || g.sw != 1 || g.P != g.H || g.Q != g.W || g.C % 8 || g.K % 8) return false;
+    const long Wp = g.W + 2 * g.pw, Hp = g.H + 2 * g.ph, PQ = (long)g.P * g.Q, last = kDFilter16BP - 1;
+    if (v.SW > 0) {
+        if (g.S != v.SW || g.R * g.S != v.tmax || Wp != v.WPC) return false;
+        taps = v.tmax; groups = 1;
+    } else {
+        if (g.S != v.tmax) return false;
+        taps = g.S; groups = g.R;
+    }
+    if (Hp * Wp > 1024 || PQ > 1024 || kDFilter16BP > PQ) return false;
+    if ((size_t)g.N * g.H * g.W * g.C * 2 >= 0x7fffffffull || (size_t)g.N * PQ * g.K * 2 >= 0x7fffffffull) return false;
+    const long span = last + (last / g.Q + 1) * (Wp - g.Q) + (Hp - g.P) * Wp;      // 64 pixels, their row ends, one image end
+    const long rows = span + (groups > 1 ? 0 : g.R - 1) * Wp + g.S;
+    return rows <= v.prf;
 }
 
 // Geometry of the small-channel strided filter-gradient kernel; false when it does not apply
@@ -563,6 +584,36 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
         }
     }
     if (pass == OWT_PASS_BWD_FILTER && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA)) {
+        for (int v = 0; v < kNumDFilter16bVariants; v++) {
+            int taps, groups;
+            if (force_tile >= 0 && force_tile != kDFilter16bFirstTile + v) continue;
+            if (!dfilter16b_fits(g, v, taps, groups)) continue;
+            const DFilter16bVariant &dv = kDFilter16bVariants[v];
+            const long KT = 32 * dv.KB * dv.WK, CT = 32 * dv.WC;
+            const long tm = cdiv(g.K, KT), ctl = cdiv(g.C, CT), steps = cdiv(dm.Kd, kDFilter16BP);
+            for (long s0 : split_ladder(tm * ctl * groups, 256)) {
+                long s = s0;
+                if (force_split > 0) s = force_split < steps ? force_split : steps;
+                else if (s > 1 && (steps / s < 2 || tm * ctl * groups * s > 1280)) break;
+                const long per = cdiv(steps, s), splits = cdiv(steps, per);
+                if (per > kDFilter16bMaxChunks) { if (force_split > 0) break; continue; }
+                Launch l; memset(&l, 0, sizeof(l));
+                l.kind = KIND_DFILTER16B; l.tile = v; l.splits = (int)splits; l.steps = (int)steps;
+                l.steps_per_split = (int)per; l.tiles_m = (int)tm; l.tiles_n = (int)(ctl * groups);
+                l.taps = taps; l.groups = groups; l.ctiles = (int)ctl;
+                if (splits > 1) {
+                    l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
+                    l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
+                }
+                l.cost = model_cost(tm * ctl * groups * splits, dv.WK * dv.WC, 1,
+                                    (double)KT * CT * kDFilter16BP * taps * per / 5.0, 1.5, splits, dm.M, dm.Ncols);
+                bool dup = false;
+                for (const Launch &o : out) dup |= o.kind == l.kind && o.tile == l.tile && o.splits == l.splits;
+                if (!dup && (l.partial_bytes <= kMaxPartialBytes || force_split > 0) &&
+                    (force_split > 0 || tm * ctl * groups * splits >= 64 || s0 == 256)) out.push_back(l);
+                if (force_split > 0) break;
+            }
+        }
         for (int v = 0; v < kNumDFilter16Variants; v++) {
             int taps, groups;
             if (force_tile >= 0 && force_tile != v) continue;
@@ -687,10 +738,16 @@ static Launch choose(const Geom &g, int pass, owt_dtype dt, const PassDims &dm, 
 // Workspace every candidate fits in (so a tuned choice never outgrows the caller's buffer).
 static size_t max_workspace(const Geom &g, int pass, const PassDims &dm, bool want_db)
 {
-    std::vector<Launch> c;
-    enumerate(g, pass, dm, want_db, c);
+    // with and without the ReLU' mask flag: a caller may size its buffer with one descriptor of a layer and call
+    // with the other (the kernels that take dz as it is are only candidates for the unmasked one)
     size_t m = 0;
-    for (const Launch &l : c) m = l.ws_bytes() > m ? l.ws_bytes() : m;
+    for (int masked = 0; masked < 2; masked++) {
+        Geom gm = g;
+        gm.masked = masked != 0;
+        std::vector<Launch> c;
+        enumerate(gm, pass, dm, want_db, c);
+        for (const Launch &l : c) m = l.ws_bytes() > m ? l.ws_bytes() : m;
+    }
     return m;
 }
 
@@ -749,6 +806,10 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         sfilter_geom(g, sg);
         sg.units_per_wg = l.steps_per_split;
         e = bf ? owt_launch_sfilter_bf16(p, sg, l.tiles_m, s) : owt_launch_sfilter_f32(p, sg, l.tiles_m, s);
+    } else if (l.kind == KIND_DFILTER16B) {
+        p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
+        p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
+        e = owt_launch_dfilter16b(l.tile, p, s);
     } else if (l.kind == KIND_DFILTER16) {
         p.Hp = g.H + 2 * g.ph; p.Wp = g.W + 2 * g.pw; p.taps = l.taps; p.groups = l.groups; p.ctiles = l.ctiles;
         p.dWp.set(p.Wp); p.dHpWp.set(p.Hp * p.Wp);
@@ -808,6 +869,12 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     if (l.kind == KIND_SFILTER)
         return snprintf(buf, n, "sfilter %s %s rows2 splitk%d grid%dx%d threads%ld", pn[pass], ds, l.splits, l.tiles_m,
                         l.splits, (long)l.tiles_m * l.splits * kSFilterNT);
+    if (l.kind == KIND_DFILTER16B) {
+        const DFilter16bVariant &v = kDFilter16bVariants[l.tile];
+        return snprintf(buf, n, "dfilter16b %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds,
+                        32 * v.KB * v.WK, 32 * v.WC, l.taps, l.groups, l.splits, l.tiles_m * l.tiles_n, l.splits,
+                        (long)l.tiles_m * l.tiles_n * l.splits * 64 * v.WK * v.WC);
+    }
     if (l.kind == KIND_DFILTER16) {
         const DFilter16Variant &v = kDFilter16Variants[l.tile];
         return snprintf(buf, n, "dfilter16 %s %s tile%dx%d taps%dx%d splitk%d grid%dx%d threads%ld", pn[pass], ds,

@@ -66,6 +66,9 @@ struct GemmParams {
     FastDiv dCpi;
 };
 
+// chunks of 64 pixels one work-group of the streamed bf16 filter-gradient kernel may walk (its per-chunk LDS table)
+constexpr int kDFilter16bMaxChunks = 256;
+
 struct bf16_t { uint16_t bits; };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }

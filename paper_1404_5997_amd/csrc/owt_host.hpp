@@ -84,6 +84,17 @@ constexpr DFilter16Variant kDFilter16Variants[kNumDFilter16Variants] = {
 constexpr int kDFilter16BP = 64;
 hipError_t owt_launch_dfilter16(int variant, const GemmParams &, hipStream_t);
 
+// The same filter gradient with the operands streamed straight into LDS (dfilter16b_inst.hip; unmasked dz, maps
+// of at most 1024 padded positions, chunks that touch at most two images).  SW > 0: all R x SW taps per
+// work-group on padded rows of WPC pixels; SW == 0: one filter row of tmax taps per work-group.  One work-group
+// per CU.  The test hook numbers these variants from kDFilter16bFirstTile.
+struct DFilter16bVariant { int WK, WC, KB, tmax, SW, WPC, prf; };
+constexpr int kNumDFilter16bVariants = 7, kDFilter16bFirstTile = 30;
+constexpr DFilter16bVariant kDFilter16bVariants[kNumDFilter16bVariants] = {
+    {2, 4, 2, 3, 0, 0, 128}, {2, 6, 2, 3, 0, 0, 128}, {2, 4, 4, 3, 0, 0, 128}, {2, 2, 4, 3, 0, 0, 128},
+    {6, 2, 1, 5, 0, 0, 224}, {3, 2, 2, 5, 0, 0, 224}, {2, 2, 3, 5, 0, 0, 224}};
+hipError_t owt_launch_dfilter16b(int variant, const GemmParams &, hipStream_t);
+
 // Dense GEMM kernel of the fully-connected shard (fcgemm_inst.hip; fp32 storage, reduction length a
 // multiple of 32): WM x WN wavefronts of MB x NB accumulator blocks of 32 x 32, occ work-groups per CU.
 // When the pass masks dy by y > 0 or wants the bias gradient, a small kernel first writes dz to `dz`

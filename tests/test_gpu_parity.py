@@ -237,6 +237,31 @@ def test_bf16_mfma_filter_gradient_kernel(variant, split):
             layer_parity(N, C, H, W, K, R, S, 1, pad, dt="bf16", seed=500 + 10 * variant + split, **kw)
 
 
+@pytest.mark.parametrize("variant,split", [(0, 1), (1, 1), (2, 1), (3, 1), (4, 1), (5, 1), (6, 1),
+                                           (0, 3), (1, 4), (2, 7), (3, 5), (4, 2), (5, 6), (6, 3)])
+def test_bf16_mfma_filter_gradient_kernel_with_operands_streamed_into_lds(variant, split):
+    # the bf16-MFMA filter gradient whose chunks go from global memory straight into LDS (per-block LDS layout,
+    # loader tables, chunks that may straddle two images), forced, alone and split over work-groups: ragged filter
+    # and channel tiles, a last chunk with few valid pixels, H != W, alpha / beta, with and without bias gradient
+    # (3-tap variants 0-3, 5-tap variants 4-6).  The kernel takes dz as it is; a call that masks dy itself
+    # (OWT_RELU) must be served by another kernel.
+    m = owt()
+    with force(30 + variant, split, m.OWT_FORCE_ONLY_DIRECT):
+        shapes = [((3, 64, 27, 27, 72, 5, 5, 2), {}), ((2, 8, 12, 21, 16, 3, 5, (1, 2)), dict(alpha=0.5, beta=-0.25)),
+                  ((1, 40, 13, 21, 64, 5, 5, 2), dict(bias=False))] if variant >= 4 else \
+                 [((4, 72, 13, 13, 136, 3, 3, 1), {}), ((2, 200, 13, 13, 192, 3, 3, 1), dict(bias=False)),
+                  ((7, 32, 13, 13, 64, 3, 3, 1), dict(alpha=1.0 / 3, beta=1.0)), ((3, 40, 17, 13, 72, 3, 3, 1), {}),
+                  ((3, 8, 6, 11, 8, 3, 3, 1), dict(alpha=0.5, beta=-0.25))]
+        for (N, C, H, W, K, R, S, pad), kw in shapes:
+            d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_BF16, m.OWT_BIAS)
+            assert m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("dfilter16b"), \
+                m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER)
+            layer_parity(N, C, H, W, K, R, S, 1, pad, dt="bf16", relu=False, seed=700 + 10 * variant + split, **kw)
+        N, C, H, W, K, R, S, pad = shapes[0][0]
+        d = m.conv_desc(N, C, H, W, K, R, S, 1, pad, m.OWT_BF16, m.OWT_BIAS | m.OWT_RELU)
+        assert not m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("dfilter16b")
+
+
 @pytest.mark.parametrize("shape,split", [
     ((5, 4, 23, 20, 8, 7, 7, 4, 2), 3), ((2, 3, 24, 24, 72, 7, 7, 4, 3), 0), ((3, 3, 36, 28, 64, 11, 11, 4, 2), 5),
     ((2, 8, 17, 12, 20, 5, 3, (2, 2), (2, 1)), 2), ((2, 3, 224, 224, 64, 11, 11, 4, 2), 0),
