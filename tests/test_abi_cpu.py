@@ -90,6 +90,14 @@ def test_workspace_queries_are_stable_and_sized_for_split_k(m):
     assert a[2] > 0 and a[2] % (384 * 1728 * 4) < 384 * 1728 * 4
     f = m.fc_desc(128, 9216, 4096, 8)
     assert m.owt_fc_workspace_bytes(f, 0) > 0     # 128 x 512 outputs cannot fill 256 CUs without split-K
+    # a layer's buffer may be sized with the descriptor that carries OWT_RELU and used by calls that pass no y (their
+    # candidates include the kernels that take dz as it is): the bound must not depend on the flag
+    for dt, shape in ((m.OWT_F32, (128, 192, 13, 13, 384, 3, 3, 1, 1)), (m.OWT_BF16, (1024, 384, 13, 13, 256, 3, 3, 1, 1)),
+                      (m.OWT_BF16, (1024, 64, 27, 27, 192, 5, 5, 1, 2)), (m.OWT_F32, (128, 3, 224, 224, 64, 11, 11, 4, 2))):
+        masked = m.conv_desc(*shape, dt, m.OWT_BIAS | m.OWT_RELU)
+        plain = m.conv_desc(*shape, dt, m.OWT_BIAS)
+        for ps in range(3):
+            assert m.owt_conv_workspace_bytes(masked, ps) == m.owt_conv_workspace_bytes(plain, ps)
 
 
 def test_scale_hyperparameters_host_call_matches_the_papers_example(m):
