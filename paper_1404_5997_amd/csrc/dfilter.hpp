@@ -15,7 +15,7 @@
 //
 // Tap groups: all R*S taps at once when R*S == TAPS, else one filter row per
 // work-group when S == TAPS (the tap count is a compile-time constant so the
-// inner loop is branch-free; other filter sizes use the gather kernel).  The pixel range is split over blockIdx.y; partial sums are
+// inner loop is branch-free; other filter sizes use the gather kernel).  The pixel range is split over work-groups (numbered so that the tiles of a split share an L2); partial sums are
 // reduced by splitk_reduce_kernel (deterministic, no atomics).
 #pragma once
 #include "igemm.hpp"
@@ -53,13 +53,11 @@ __global__ void __launch_bounds__(64 * WK * WC, OCC) dfilter_kernel(const GemmPa
     const int li = lane & 31, lh = lane >> 5;
     const int wk0 = (wave / WC) * 32, wc0 = (wave % WC) * 32;
 
-    const int ntiles = p.tiles_m * p.tiles_n;
-    const int b = blockIdx.x, xcd = b & 7;
-    const int logical = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + (b >> 3);
+    int logical, split;
+    if (!owt_split_major_wg(p.tiles_m * p.tiles_n, p.splits, logical, split)) return;
     const int kt = logical / p.tiles_n, rem = logical - kt * p.tiles_n;
     const int grp = rem / p.ctiles, ct = rem - grp * p.ctiles;
     const int k0 = kt * KT, c0 = ct * CT;
-    const int split = blockIdx.y;
     const int ch_beg = split * p.ksteps_per_split, ch_end = min(p.ksteps, ch_beg + p.ksteps_per_split);
 
     const int RS = g.R * g.S, Wp = p.Wp, npix = p.Kd;

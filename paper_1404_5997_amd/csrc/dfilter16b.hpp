@@ -61,13 +61,11 @@ __global__ void __launch_bounds__(64 * WK * WC, 1) dfilter16b_kernel(const GemmP
     const int grp16 = lane >> 4, i16 = lane & 15;                // 16-lane group and position in it
     const int wkw = wave / WC, wcw = wave % WC;
 
-    const int ntiles = p.tiles_m * p.tiles_n;
-    const int b = blockIdx.x, xcd = b & 7;
-    const int logical = xcd * (ntiles >> 3) + min(xcd, ntiles & 7) + (b >> 3);
+    int logical, split;
+    if (!owt_split_major_wg(p.tiles_m * p.tiles_n, p.splits, logical, split)) return;
     const int kt = logical / p.tiles_n, rem = logical - kt * p.tiles_n;
     const int grp = rem / p.ctiles, ct = rem - grp * p.ctiles;
     const int k0 = kt * KT, c0 = ct * CT;
-    const int split = blockIdx.y;
     const int ch_beg = split * p.ksteps_per_split, ch_end = min(p.ksteps, ch_beg + p.ksteps_per_split);
 
     const int RS = g.R * g.S, Wp = p.Wp, npix = p.Kd;

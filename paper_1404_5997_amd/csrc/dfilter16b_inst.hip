@@ -8,7 +8,7 @@ template <int V>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     constexpr DFilter16bVariant v = kDFilter16bVariants[V];
-    const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
+    const dim3 grid(owt_split_major_grid(p.tiles_m * p.tiles_n, p.splits));
     hipLaunchKernelGGL((dfilter16b_kernel<v.WK, v.WC, v.KB, v.tmax, v.SW, v.WPC, v.prf>), grid, dim3(64 * v.WK * v.WC), 0, s, p);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && p.splits > 1) e = launch_splitk_reduce<EpiFilter>(p, s);

@@ -8,7 +8,7 @@ template <int V>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     constexpr DFilter2Variant v = kDFilter2Variants[V];
-    const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
+    const dim3 grid(owt_split_major_grid(p.tiles_m * p.tiles_n, p.splits));
     if (p.mask) return hipErrorInvalidValue;       // the planner sends masked calls to dfilter.hpp
     hipLaunchKernelGGL((dfilter2_kernel<v.WK, v.WP, v.tmax, v.SW, v.WPC, v.prows>), grid, dim3(64 * v.WK * v.WP), 0, s, p);
     hipError_t e = hipGetLastError();

@@ -21,7 +21,7 @@ template <int V>
 static hipError_t go(const GemmParams &p, hipStream_t s)
 {
     constexpr DFilterVariant v = kDFilterVariants[V];
-    const dim3 grid(p.tiles_m * p.tiles_n, p.splits);
+    const dim3 grid(owt_split_major_grid(p.tiles_m * p.tiles_n, p.splits));
     // the low-vector-ALU form of the loader and fetch: fp32 storage, chunks cut per image, one filter row per
     // work-group, dz not masked by the call, tables and byte offsets within their ranges
     const long IP = (long)p.Hp * p.Wp, PQ = (long)p.g.P * p.g.Q;

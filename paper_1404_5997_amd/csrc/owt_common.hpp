@@ -91,6 +91,25 @@ __device__ __forceinline__ float4 load4(const bf16_t *p, int off)
     return make_float4(__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u),
                        __uint_as_float(v.y << 16), __uint_as_float(v.y & 0xffff0000u));
 }
+// Work-group numbering of the filter-gradient kernels whose pixel range is split over work-groups.  The tiles of
+// one split all read the same dz and x chunks (a dz chunk once per channel tile and filter row, an x chunk once per
+// filter tile), so they should run at the same time behind the same L2.  The grid is one-dimensional with
+// owt_split_major_grid(tiles, splits) work-groups, work-group L runs on XCD L % 8, and the (split, tile) pairs,
+// split-major, are dealt to the XCDs in eight contiguous runs of equal length (+-1): an XCD works through whole
+// splits, tile after tile.  (Numbered tile-major over a two-dimensional grid, the few tiles of a split land on
+// different XCDs and every chunk is fetched once per tile: the counters showed 3-7 times the compulsory bytes.)
+// Returns false for the padding work-groups at the end of the grid, which must exit before any barrier.
+__host__ __device__ inline int owt_split_major_grid(int tiles, int splits) { return 8 * ((tiles * splits + 7) / 8); }
+__device__ __forceinline__ bool owt_split_major_wg(int ntiles, int splits, int &tile, int &split)
+{
+    const int total = ntiles * splits, xcd = blockIdx.x & 7, jx = blockIdx.x >> 3;
+    if (jx >= (total >> 3) + (xcd < (total & 7) ? 1 : 0)) return false;
+    const int pair = xcd * (total >> 3) + min(xcd, total & 7) + jx;
+    split = pair / ntiles;
+    tile = pair - split * ntiles;
+    return true;
+}
+
 // 16 bytes through a raw buffer descriptor: a byte offset outside [0, bytes) reads as zeros without touching
 // memory, so bounds need no branch, no exec masking and no zeroing of the destination.
 typedef unsigned int owt_u32x4 __attribute__((ext_vector_type(4)));
