@@ -58,7 +58,7 @@ bool fill_geom(Geom &g, int N, int C, int H, int W, int K, int R, int S, int sh,
 // forward / backward-data, as the panel-resident kernel (dconv.hpp).  Every
 // (kernel, tile, split) that fits is a candidate; a cost model picks one unless
 // owt_conv_autotune has timed them for this descriptor.
-enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11, KIND_SFILTER2 = 12, KIND_DFILTER16B = 13 };
+enum { KIND_GATHER = 0, KIND_DIRECT = 1, KIND_DFILTER = 2, KIND_SFILTER = 3, KIND_SCONV = 4, KIND_DIRECT16 = 5, KIND_DFILTER16 = 6, KIND_SCONV16 = 7, KIND_SFILTER16 = 8, KIND_FCGEMM = 9, KIND_DFILTER2 = 10, KIND_SCONV2 = 11, KIND_SFILTER2 = 12, KIND_DFILTER16B = 13, KIND_SFILTER16B = 14 };
 
 struct PassDims { long M, Ncols, Kd; bool va, vb; };
 
@@ -257,6 +257,18 @@ static bool sfilter16_geom(const Geom &g, SFilter16Geom &sg)
     return sg.NB <= (kSFilter16NT / 64) * kSFilter16CB && lds <= 150 * 1024 && sg.ROWS < 256 &&
            (long)sg.ROWS * (g.W * g.C / 4) <= (long)kSFilter16NT * kSFilter16PNP &&
            sg.DZP <= (kSFilter16NT / 8) * kSFilter16DNP;
+}
+
+// The bf16 first-layer filter-gradient kernel whose units stream straight into two LDS stages: dz taken as it is,
+// 16-byte aligned row data in the panel, both stages within LDS, the loaders' instruction counts, 32-bit byte
+// offsets inside one image.
+static bool sfilter16b_fits(const Geom &g, const SFilter16Geom &sg)
+{
+    const long pp8 = ((sg.PITCH + 7) & ~7) / 8, pan_inst = ((long)sg.ROWS * pp8 + 63) / 64, dz_inst = sg.DZP / 8;
+    const size_t lds = (size_t)2 * (pan_inst + dz_inst) * 1024 + (size_t)sg.DZP * 4;
+    return !g.masked && (g.pw * g.C + sg.LPAD) % 8 == 0 && (g.W * g.C) % 8 == 0 && pan_inst <= 8 * kSFilter16bPNI &&
+           dz_inst <= 8 * kSFilter16bDNI && lds <= 158 * 1024 && (size_t)g.H * g.W * g.C * 2 < 0x40000000ull &&
+           (size_t)g.P * g.Q * g.K * 2 < 0x40000000ull;
 }
 
 // Geometry of the small-channel strided forward kernel; false when it does not apply.
@@ -496,9 +508,13 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (force_split > 0) break;
         }
     }
+    // test hook: tile 24 = only the register-staged bf16 first-layer filter-gradient kernel, 25 = only the one that
+    // streams its units straight into LDS
     SFilter16Geom sf16g;
-    if (pass == OWT_PASS_BWD_FILTER && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA) && (g.sh > 1 || g.sw > 1) &&
-        sfilter16_geom(g, sf16g)) {
+    const bool sf16_ok = pass == OWT_PASS_BWD_FILTER && !no_direct && !forced(OWT_FORCE_NO_BF16_MFMA) && (g.sh > 1 || g.sw > 1) &&
+                         sfilter16_geom(g, sf16g);
+    for (int form = 0; form < 2 && sf16_ok; form++) {
+        if (form == 0 ? force_tile == 25 : (force_tile == 24 || !sfilter16b_fits(g, sf16g))) continue;
         const long ktiles = cdiv(g.K, 64);
         for (long target : {256L, 512L, 1024L}) {
             long wgs = target / ktiles > 0 ? target / ktiles : 1;
@@ -506,13 +522,13 @@ static void enumerate(const Geom &g, int pass, const PassDims &dm, bool want_db,
             if (wgs > sf16g.units) wgs = sf16g.units;
             const long per = cdiv(sf16g.units, wgs), splits = cdiv(sf16g.units, per);
             Launch l; memset(&l, 0, sizeof(l));
-            l.kind = KIND_SFILTER16; l.tile = 0; l.splits = (int)splits; l.steps = sf16g.units; l.steps_per_split = (int)per;
+            l.kind = form ? KIND_SFILTER16B : KIND_SFILTER16; l.tile = 0; l.splits = (int)splits; l.steps = sf16g.units; l.steps_per_split = (int)per;
             l.tiles_m = (int)ktiles; l.tiles_n = 1;
             if (splits > 1) {
                 l.partial_bytes = pad256((size_t)splits * dm.M * dm.Ncols * 4);
                 l.dbias_bytes = want_db ? pad256((size_t)splits * dm.M * 4) : 0;
             }
-            l.cost = model_cost(ktiles * splits, 8, 1, 64.0 * sf16g.NB * 32 * sf16g.DZP * per / 5.0, 1.0, splits, dm.M, dm.Ncols);
+            l.cost = model_cost(ktiles * splits, 8, 1, 64.0 * sf16g.NB * 32 * sf16g.DZP * per / 5.0, form ? 1.3 : 1.0, splits, dm.M, dm.Ncols);
             bool dup = false;
             for (const Launch &o : out) dup |= o.kind == l.kind && o.splits == l.splits;
             if (!dup) out.push_back(l);
@@ -791,6 +807,11 @@ static owt_status launch(const Geom &g, int pass, owt_dtype dt, const PassDims &
         p.splits = 1; p.partial = nullptr;
         e = bf ? owt_launch_sconv_bf16(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s)
                : owt_launch_sconv_f32(p, sg, l.tiles_m, l.tiles_n, (float *)ws, s);
+    } else if (l.kind == KIND_SFILTER16B) {
+        SFilter16Geom sg;
+        sfilter16_geom(g, sg);
+        sg.units_per_wg = l.steps_per_split;
+        e = owt_launch_sfilter16b(p, sg, l.tiles_m, s);
     } else if (l.kind == KIND_SFILTER16) {
         SFilter16Geom sg;
         sfilter16_geom(g, sg);
@@ -860,6 +881,9 @@ static int describe(char *buf, size_t n, int pass, owt_dtype dt, const PassDims 
     if (l.kind == KIND_SCONV)
         return snprintf(buf, n, "sconv %s %s band%d grid%dx%d threads%ld", pn[pass], ds, kSConvBand, l.tiles_m, l.tiles_n,
                         (long)l.tiles_m * l.tiles_n * kSConvNT);
+    if (l.kind == KIND_SFILTER16B)
+        return snprintf(buf, n, "sfilter16b %s %s rows%d splitk%d grid%dx%d threads%ld", pn[pass], ds, kSFilter16TP, l.splits,
+                        l.tiles_m, l.splits, (long)l.tiles_m * l.splits * kSFilter16NT);
     if (l.kind == KIND_SFILTER16)
         return snprintf(buf, n, "sfilter16 %s %s rows%d splitk%d grid%dx%d threads%ld", pn[pass], ds, kSFilter16TP, l.splits,
                         l.tiles_m, l.splits, (long)l.tiles_m * l.splits * kSFilter16NT);

@@ -126,6 +126,7 @@ hipError_t owt_launch_sfilter_bf16(const GemmParams &, const SFilterGeom &, int 
 // Small-channel strided forward kernel (sconv_inst.hip); w2 is K x KSLOTS floats of workspace.
 struct SConvGeom;
 hipError_t owt_launch_sconv_f32(const GemmParams &, const SConvGeom &, int ktiles, int nwg, float *w2, hipStream_t);
+hipError_t owt_launch_sfilter16b(const GemmParams &, const SFilter16Geom &, int ktiles, hipStream_t);
 hipError_t owt_launch_sfilter2_f32(const GemmParams &, const SFilterGeom &, int ktiles, hipStream_t);
 hipError_t owt_launch_sconv2_f32(const GemmParams &, const SConvGeom &, int ktiles, int nwg, float *w2, hipStream_t);
 hipError_t owt_launch_sconv_bf16(const GemmParams &, const SConvGeom &, int ktiles, int nwg, float *w2, hipStream_t);

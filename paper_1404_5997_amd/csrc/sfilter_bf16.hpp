@@ -24,6 +24,9 @@ struct SFilter16Geom {
 };
 constexpr int kSFilter16NT = 512, kSFilter16TP = 4, kSFilter16PNP = 8, kSFilter16DNP = 4, kSFilter16CB = 2;
 
+// direct-to-LDS instructions per wavefront and unit (panel, dz) of the form that streams its units into LDS (sfilter16b.hpp)
+constexpr int kSFilter16bPNI = 6, kSFilter16bDNI = 4;
+
 template <int UNUSED = 0>
 __global__ void __launch_bounds__(kSFilter16NT, 1) sfilter16_kernel(const GemmParams p, const SFilter16Geom sg)
 {

@@ -305,6 +305,20 @@ def test_strided_small_channel_kernels(shape, split):
             if tile == 23:
                 assert not m.owt_conv_plan_describe(d, m.OWT_PASS_BWD_FILTER).startswith("sfilter2")
                 layer_parity(N, C, H, W, K, R, S, stride, pad, seed=280 + split)
+    # ... and the two bf16-MFMA filter-gradient kernels (the second one when the row data is 16-byte aligned in LDS)
+    if K % 8 == 0:
+        dbn = m.conv_desc(N, C, H, W, K, R, S, stride, pad, m.OWT_BF16, m.OWT_BIAS)
+        for tile, name in ((24, "sfilter16 "), (25, "sfilter16b ")):
+            with force(tile, split, m.OWT_FORCE_ONLY_DIRECT):
+                got = m.owt_conv_plan_describe(dbn, m.OWT_PASS_BWD_FILTER)
+                pw = pad[1] if isinstance(pad, tuple) else pad
+                fits_b = (pw * C + (4 - (pw * C) % 4) % 4) % 8 == 0 and (W * C) % 8 == 0
+                if tile == 24 or fits_b:
+                    assert got.startswith(name), got
+                else:
+                    assert not got.startswith("sfilter16b"), got
+                layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, seed=290 + split)
+                layer_parity(N, C, H, W, K, R, S, stride, pad, dt="bf16", relu=False, bias=False, alpha=0.5, beta=-0.25, seed=295 + split)
 
 
 def test_autotune_keeps_results_and_is_remembered():
