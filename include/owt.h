@@ -257,7 +257,8 @@ const char *owt_last_error(void);
  * (-1, 0, 0): `tile` >= 0 restricts the candidates to that tile / variant number of whichever kernel
  * family serves the pass (families with a variant table of their own count from 0; 10..12 are the fp32 filter
  * gradient with the pixel split inside the work-group, 16..19 the dense shard kernel's four tiles, 20/21 and
- * 22/23 the two fp32 first-layer forward / filter-gradient kernels, 30..36 the bf16 filter gradient that
+ * 22/23 the two fp32 first-layer forward / filter-gradient kernels, 24/25 the two bf16 first-layer
+ * filter-gradient kernels, 30..36 the bf16 filter gradient that
  * streams its operands into LDS), `splitk` > 0 forces the
  * split count of the reduction (clamped to the number of reduction steps), `flags` is a set of
  * OWT_FORCE_* bits.  While an override is active, tuned and cached plans are ignored.  The three
