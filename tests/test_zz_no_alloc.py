@@ -18,19 +18,21 @@ def say(*a):
     sys.stdout.flush()
 
 
-def _one(m, shape, seed, alpha, beta, relu):
+def _one(m, shape, seed, alpha, beta, relu, dt="f32"):
+    import oracle
     N, C, H, W, K, R, S, stride, pad = shape
-    case = ConvCase(N, C, H, W, K, R, S, stride, pad, "f32", True, relu)
+    case = ConvCase(N, C, H, W, K, R, S, stride, pad, dt, True, relu)
     g = np.random.default_rng(seed)
-    x = g.standard_normal(case.shape_x, dtype=np.float32)
-    dy = g.standard_normal(case.shape_y, dtype=np.float32)
-    y = g.standard_normal(case.shape_y, dtype=np.float32) if relu else None
+    r = (lambda a: oracle.round_bf16(a)) if dt == "bf16" else (lambda a: a)
+    x = r(g.standard_normal(case.shape_x, dtype=np.float32))
+    dy = r(g.standard_normal(case.shape_y, dtype=np.float32))
+    y = r(g.standard_normal(case.shape_y, dtype=np.float32)) if relu else None
     dw0 = g.standard_normal(case.shape_w, dtype=np.float32)
     db0 = g.standard_normal((K,), dtype=np.float32)
     say("static-scratch case", shape, "plan:", m.owt_conv_plan_describe(case.desc, m.OWT_PASS_BWD_FILTER))
     dw_ref, db_ref = case.bwd_filter(x, dy, y, alpha, beta, dw0, db0)          # caller workspace
     dw, db = to_dev(dw0), to_dev(db0)
-    m.owt_conv_bwd_filter_static(case.desc, to_dev(x), to_dev(dy), to_dev(y), alpha, beta, dw, db)
+    m.owt_conv_bwd_filter_static(case.desc, to_dev(x, dt), to_dev(dy, dt), to_dev(y, dt), alpha, beta, dw, db)
     torch.cuda.synchronize()
     e1 = assert_close(to_host(dw), dw_ref, "f32", "dw (static scratch) %s" % (shape,))
     e2 = assert_close(to_host(db), db_ref, "f32", "db (static scratch) %s" % (shape,))
@@ -50,3 +52,6 @@ def test_static_scratch_filter_gradient_equals_the_workspace_call_twice_in_a_row
     _one(m, (4, 40, 13, 13, 136, 3, 3, 1, 1), 2, 0.5, -0.25, False)
     with force(-1, 5):
         _one(m, (3, 12, 15, 15, 36, 3, 3, 2, 1), 3, 1.0 / 3, 1.0, True)
+    # bf16 storage, dz taken as it is: the kernels that stream their operands straight into LDS
+    _one(m, (64, 192, 13, 13, 384, 3, 3, 1, 1), 4, 1.0 / 64, 0.0, False, "bf16")
+    _one(m, (4, 3, 64, 64, 64, 11, 11, 4, 2), 5, 0.5, -0.25, False, "bf16")
